@@ -1,0 +1,133 @@
+"""Seeded synthetic inputs for the attention hot path, shared by the CPU oracle's tests and the HIP path.
+
+This module holds none of the method's arithmetic: it only produces bf16 bit patterns
+(as numpy uint16) for Q, K, V and dO in the `[B, N, H, d]` layout, plus the workload table.
+It imports neither the oracle nor the HIP binding, so both sides see byte-identical inputs.
+
+Workload shapes follow the paper's video tokenisation (Sec. 3, "Video Transformer":
+N = T/t * H/h * W/w cubes) and the VideoMAE setting of Sec. 5.5 (16 frames, cubes of
+2x16x16 at 224^2 -> 8*14*14 = 1568 tokens).  The paper's activations come from real video
+datasets with pretrained weights; here iid N(0,1) values rounded to bf16 stand in for them.
+
+Generator: counter based.  Element `i` of stream `s` under `seed` draws two 64-bit words from
+splitmix64 on a key built from (seed, s, i), maps them to uniforms in (0,1] and [0,1), and
+applies the Box-Muller cosine branch in fp64; the result is rounded to fp32 and then to bf16
+with round-to-nearest-even.  No state is kept, so any slice can be produced on its own.
+"""
+from __future__ import annotations
+
+import dataclasses
+import math
+
+import numpy as np
+
+_MASK = np.uint64(0xFFFFFFFFFFFFFFFF)
+_GOLD = np.uint64(0x9E3779B97F4A7C15)
+_M1 = np.uint64(0xBF58476D1CE4E5B9)
+_M2 = np.uint64(0x94D049BB133111EB)
+
+
+def _mix64(z: np.ndarray) -> np.ndarray:
+    """splitmix64 finaliser on an array of uint64 (wraps modulo 2^64)."""
+    z = (z ^ (z >> np.uint64(30))) * _M1
+    z = (z ^ (z >> np.uint64(27))) * _M2
+    return z ^ (z >> np.uint64(31))
+
+
+def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """fp32 -> bf16 bit patterns (uint16), round to nearest even. NaN is not expected here."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    rounding = np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))
+    return ((u + rounding) >> np.uint32(16)).astype(np.uint16)
+
+
+def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    """bf16 bit patterns (uint16) -> fp32, exact."""
+    return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def bf16_bits_to_f64(b: np.ndarray) -> np.ndarray:
+    """bf16 bit patterns (uint16) -> fp64, exact."""
+    return bf16_bits_to_f32(b).astype(np.float64)
+
+
+def normal_bf16_bits(seed: int, stream: int, count: int, offset: int = 0, chunk: int = 1 << 22) -> np.ndarray:
+    """`count` iid N(0,1) draws, elements offset..offset+count-1 of (seed, stream), as bf16 bits."""
+    out = np.empty(count, dtype=np.uint16)
+    with np.errstate(over="ignore"):
+        key = _mix64(np.uint64(seed & 0xFFFFFFFFFFFFFFFF) * _GOLD + np.uint64(stream + 1) * _M2)
+        for start in range(0, count, chunk):
+            n = min(chunk, count - start)
+            idx = np.arange(offset + start, offset + start + n, dtype=np.uint64)
+            a = _mix64(key + (idx * np.uint64(2) + np.uint64(1)) * _GOLD)
+            b = _mix64(key + (idx * np.uint64(2) + np.uint64(2)) * _GOLD)
+            # u1 in (0,1], u2 in [0,1): 53-bit mantissas
+            u1 = ((a >> np.uint64(11)).astype(np.float64) + 1.0) * (1.0 / 9007199254740992.0)
+            u2 = (b >> np.uint64(11)).astype(np.float64) * (1.0 / 9007199254740992.0)
+            z = np.sqrt(-2.0 * np.log(u1)) * np.cos((2.0 * math.pi) * u2)
+            out[start:start + n] = f32_to_bf16_bits(z.astype(np.float32))
+    return out
+
+
+@dataclasses.dataclass(frozen=True)
+class Workload:
+    """One attention problem: Q, K, V, dO of shape [B, N, H, d] bf16; non-causal self-attention."""
+    name: str
+    B: int
+    H: int
+    N: int
+    d: int
+    scale: float
+    seed: int
+    k_mul: float = 1.0   # K is multiplied by this power of two after rounding (exact in bf16)
+    note: str = ""
+
+    @property
+    def shape(self):
+        return (self.B, self.N, self.H, self.d)
+
+    @property
+    def base(self) -> float:
+        """B*H*N^2*d: fwd is 4*base flops, bwd 10*base, fwd+bwd 14*base."""
+        return float(self.B) * self.H * self.N * self.N * self.d
+
+
+WORKLOADS = {
+    w.name: w
+    for w in [
+        Workload("vitb_clip", 1, 12, 1568, 64, 0.125, 230916691,
+                 note="one ViT-B layer on one 16-frame 224^2 clip, cubes 2x16x16 -> 8*14*14 tokens"),
+        Workload("vitb_batch", 32, 12, 1568, 64, 0.125, 230916692,
+                 note="ViT-B video training batch of 32 clips"),
+        Workload("vitl_batch_peaky", 16, 16, 1568, 64, 0.125, 230916693, k_mul=2.0,
+                 note="ViT-L heads, K doubled for a peakier softmax"),
+        Workload("vitb_long", 8, 12, 3136, 64, 0.125, 230916694,
+                 note="32 frames -> 16*14*14 tokens"),
+        Workload("vith_d80", 8, 16, 1568, 80, 1.0 / math.sqrt(80.0), 230916695,
+                 note="ViT-H-width head dim 80"),
+        Workload("vitl_336", 4, 16, 3528, 64, 0.125, 230916696,
+                 note="16 frames at 336^2 -> 8*21*21 tokens"),
+    ]
+}
+
+STREAMS = {"q": 0, "k": 1, "v": 2, "dO": 3}
+
+
+def make_inputs(w: Workload, names=("q", "k", "v", "dO")) -> dict:
+    """bf16 bit patterns (uint16 arrays of shape [B,N,H,d]) for the requested tensors of a workload."""
+    count = w.B * w.N * w.H * w.d
+    out = {}
+    for name in names:
+        bits = normal_bf16_bits(w.seed, STREAMS[name], count)
+        if name == "k" and w.k_mul != 1.0:
+            scaled = bf16_bits_to_f32(bits) * np.float32(w.k_mul)
+            bits = f32_to_bf16_bits(scaled)   # exact: a power-of-two multiple
+        out[name] = bits.reshape(w.shape)
+    return out
+
+
+def small_workload(B, H, N, d, seed, scale=None, k_mul=1.0, name=None) -> Workload:
+    """A reduced problem with the same recipe, for parity cases the oracle finishes in seconds."""
+    if scale is None:
+        scale = 1.0 / math.sqrt(d)
+    return Workload(name or f"small_B{B}_H{H}_N{N}_d{d}", B, H, N, d, scale, seed, k_mul)
