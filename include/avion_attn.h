@@ -1,0 +1,94 @@
+/*
+ * avion_attn.h -- C ABI of the MI355X (gfx950) exact, O(N)-memory multi-head self-attention.
+ *
+ * The operation is the attention core of the plain joint space-time ViT of the paper (Sec. 3,
+ * "Video Transformer": N = T/t * H/h * W/w tokens; each encoder layer holds one multi-head
+ * self-attention), made memory efficient as in Sec. 3, "Flash Attention": the softmax weights are
+ * never stored (memory O(N) instead of O(N^2)) and the work is done block by block out of on-chip
+ * memory, the block results being combined into the exact final output (Sec. 1).
+ *
+ * Per (batch b, head h), with s_ij = scale * <q_i, k_j>, P = row-softmax(S):
+ *     forward :  O = P V ,  LSE_i = ln sum_j exp(s_ij)
+ *     backward:  dV = P^T dO ; dP = dO V^T ; dS = P o (dP - rowsum(dO o O)) ;
+ *                dQ = scale * dS K ; dK = scale * dS^T Q
+ * Non-causal, no mask, no dropout, same N for queries and keys.
+ *
+ * Common rules for every entry point
+ *   - All tensor pointers are DEVICE pointers owned by the caller.  The library never allocates,
+ *     frees or keeps them.  q, k, v, o, dO, dq, dk, dv are bf16 in the layout [B, N, H, d],
+ *     contiguous (token stride H*d elements, head stride d).  lse is fp32 in the layout [B, H, N]
+ *     (natural logarithm of the sum of exponentials of the *scaled* scores).
+ *   - Every tensor pointer must be 16-byte aligned.  Outputs must not alias inputs or each other.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls only enqueue work
+ *     on that stream and return; they never synchronise.
+ *   - Supported head dims: d = 64 and d = 80.  Any B, H, N >= 1 with B*H <= 65535*... see
+ *     AVION_EUNSUPPORTED below; N up to 2^24.
+ *   - Return value: AVION_OK (0) or a negative AVION_E* code.  On an argument error nothing is
+ *     launched and no output is touched.  No exception crosses the boundary.
+ *   - NaN/Inf in the inputs are not checked and propagate.
+ *   - Arithmetic: bf16 MFMA contractions with fp32 accumulation; softmax statistics, LSE and the
+ *     row sums of dO o O in fp32; P and dS are rounded to bf16 (nearest even) before they enter a
+ *     contraction; outputs are rounded to bf16 once, at the final store.
+ *   - Results are bit-reproducible from run to run (no atomics anywhere).
+ */
+#ifndef AVION_ATTN_H
+#define AVION_ATTN_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define AVION_OK 0
+#define AVION_EINVAL (-1)       /* null pointer; B, H or N < 1; scale not finite or <= 0            */
+#define AVION_EUNSUPPORTED (-2) /* d not in {64, 80}; misaligned pointer; N > 2^24; B*H > 2^24     */
+#define AVION_EWORKSPACE (-3)   /* workspace NULL, misaligned (256 B) or smaller than required      */
+#define AVION_EHIP (-4)         /* a HIP launch failed; avion_last_hip_error() has the runtime text */
+
+/* Library version as major*10000 + minor*100 + patch. */
+int avion_version(void);
+
+/* Static text for a return code (never NULL). */
+const char *avion_strerror(int code);
+
+/* Text of the last HIP runtime error seen by this thread inside the library ("" if none). */
+const char *avion_last_hip_error(void);
+
+/*
+ * Forward (Sec. 3, "Flash Attention"; Sec. 1 for the exactness of the block-wise combination).
+ *   q, k, v : in,  bf16 [B,N,H,d]
+ *   o       : out, bf16 [B,N,H,d], fully overwritten
+ *   lse     : out, fp32 [B,H,N],   fully overwritten; needed by avion_attn_bwd
+ *   scale   : multiplies the dot products (1/sqrt(d) in a ViT); must be finite and > 0
+ * Extra device memory used: none.
+ */
+int avion_attn_fwd(const void *q, const void *k, const void *v, void *o, float *lse,
+                   int B, int H, int N, int d, float scale, void *stream);
+
+/*
+ * Bytes of device workspace avion_attn_bwd needs for this shape: B*H*N fp32 (the row sums of
+ * dO o O) rounded up to 256 bytes -- linear in N, never N^2.  Returns 0 for an unsupported shape.
+ */
+size_t avion_attn_bwd_workspace_bytes(int B, int H, int N, int d);
+
+/*
+ * Backward.  P is rebuilt block by block from q, k and the saved lse, so no N x N matrix is read
+ * or written (Sec. 3: the weights stay implicit; Sec. 4.1: the attention memory is removed).
+ *   q, k, v     : in,  bf16 [B,N,H,d]  (the forward's inputs)
+ *   o, lse      : in,  exactly as avion_attn_fwd wrote them
+ *   dO          : in,  bf16 [B,N,H,d]  gradient of the loss with respect to o
+ *   dq, dk, dv  : out, bf16 [B,N,H,d], fully overwritten
+ *   workspace   : device scratch, 256-byte aligned, at least avion_attn_bwd_workspace_bytes(...)
+ *                 bytes; contents on entry are ignored, contents on return are unspecified.
+ *                 Two calls that overlap in time on the GPU must not share a workspace.
+ */
+int avion_attn_bwd(const void *q, const void *k, const void *v, const void *o, const float *lse,
+                   const void *dO, void *dq, void *dk, void *dv,
+                   int B, int H, int N, int d, float scale,
+                   void *workspace, size_t workspace_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AVION_ATTN_H */

@@ -1,0 +1,118 @@
+"""MI355X-native exact O(N)-memory attention (forward + backward) behind a C ABI.
+
+`attn_fwd`, `attn_bwd`, `attn_bwd_workspace_bytes` mirror the entry points of
+`include/avion_attn.h` one to one.  This module only marshals arguments (device pointers, sizes,
+the current HIP stream); every step of the computation runs in the HIP kernels of
+`libavion_attn.so`.  There is no CPU or PyTorch fallback: if the library is missing, loading fails.
+PyTorch is used for device memory and streams only.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libavion_attn.so")
+
+OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, -1, -2, -3, -4
+
+_lib = None
+
+
+class AvionError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"avion_attn error {code}: {text}")
+        self.code = code
+
+
+def load_library() -> ctypes.CDLL:
+    """Load the HIP library built in-tree. Raises if it has not been built (no fallback)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()' "
+                "or python paper_2309_16669_amd/build.py); there is no fallback path")
+        lib = ctypes.CDLL(LIB_PATH)
+        p, i, f, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
+        lib.avion_version.restype = i
+        lib.avion_version.argtypes = []
+        lib.avion_strerror.restype = ctypes.c_char_p
+        lib.avion_strerror.argtypes = [i]
+        lib.avion_last_hip_error.restype = ctypes.c_char_p
+        lib.avion_last_hip_error.argtypes = []
+        lib.avion_attn_fwd.restype = i
+        lib.avion_attn_fwd.argtypes = [p, p, p, p, p, i, i, i, i, f, p]
+        lib.avion_attn_bwd_workspace_bytes.restype = sz
+        lib.avion_attn_bwd_workspace_bytes.argtypes = [i, i, i, i]
+        lib.avion_attn_bwd.restype = i
+        lib.avion_attn_bwd.argtypes = [p, p, p, p, p, p, p, p, p, i, i, i, i, f, p, sz, p]
+        _lib = lib
+    return _lib
+
+
+def version() -> int:
+    return int(load_library().avion_version())
+
+
+def strerror(code: int) -> str:
+    return load_library().avion_strerror(int(code)).decode()
+
+
+def _check(rc: int):
+    if rc != OK:
+        lib = load_library()
+        text = strerror(rc)
+        if rc == EHIP:
+            text += ": " + lib.avion_last_hip_error().decode()
+        raise AvionError(rc, text)
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream_handle(stream):
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _require(t, name, dtype, shape=None):
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live on the GPU")
+    if t.dtype != dtype:
+        raise ValueError(f"{name} must be {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name} must have shape {tuple(shape)}, got {tuple(t.shape)}")
+
+
+def attn_bwd_workspace_bytes(B: int, H: int, N: int, d: int) -> int:
+    return int(load_library().avion_attn_bwd_workspace_bytes(B, H, N, d))
+
+
+def attn_fwd(q, k, v, o, lse, scale: float, stream=None) -> None:
+    """avion_attn_fwd on torch tensors: q,k,v,o bf16 [B,N,H,d] on the GPU; lse fp32 [B,H,N]."""
+    import torch
+    B, N, H, d = q.shape
+    for t, n in ((q, "q"), (k, "k"), (v, "v"), (o, "o")):
+        _require(t, n, torch.bfloat16, (B, N, H, d))
+    _require(lse, "lse", torch.float32, (B, H, N))
+    _check(load_library().avion_attn_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), B, H, N, d,
+                                         float(scale), _stream_handle(stream)))
+
+
+def attn_bwd(q, k, v, o, lse, dO, dq, dk, dv, scale: float, workspace, stream=None) -> None:
+    """avion_attn_bwd on torch tensors; `workspace` is a uint8 GPU tensor of at least
+    attn_bwd_workspace_bytes(B,H,N,d) bytes."""
+    import torch
+    B, N, H, d = q.shape
+    for t, n in ((q, "q"), (k, "k"), (v, "v"), (o, "o"), (dO, "dO"), (dq, "dq"), (dk, "dk"), (dv, "dv")):
+        _require(t, n, torch.bfloat16, (B, N, H, d))
+    _require(lse, "lse", torch.float32, (B, H, N))
+    _require(workspace, "workspace", torch.uint8)
+    _check(load_library().avion_attn_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(dO),
+                                         _ptr(dq), _ptr(dk), _ptr(dv), B, H, N, d, float(scale),
+                                         _ptr(workspace), workspace.numel(), _stream_handle(stream)))

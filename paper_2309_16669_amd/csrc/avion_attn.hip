@@ -1,0 +1,209 @@
+// C ABI of the gfx950 attention library: argument checks, kernel-instance selection, launches.
+// See include/avion_attn.h for the contract of every entry point.
+#include "avion_attn.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+
+#include "avion_bwd.h"
+#include "avion_fwd.h"
+
+namespace {
+
+thread_local char g_hip_error[256] = "";
+
+int hip_fail(hipError_t e, const char* what)
+{
+    std::snprintf(g_hip_error, sizeof g_hip_error, "%s: %s", what, hipGetErrorString(e));
+    return AVION_EHIP;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_shape(int B, int H, int N, int d, float scale)
+{
+    if (B < 1 || H < 1 || N < 1) return AVION_EINVAL;
+    if (!(scale > 0.f) || !std::isfinite(scale)) return AVION_EINVAL;
+    if (d != 64 && d != 80) return AVION_EUNSUPPORTED;
+    if (N > (1 << 24) || (long long)B * H > (1 << 24)) return AVION_EUNSUPPORTED;
+    return AVION_OK;
+}
+
+// Tuning knob for sweeps: AVION_VARIANT_<NAME>=<int> picks a kernel instance; unset = default.
+int variant(const char* name, int dflt)
+{
+    char key[64];
+    std::snprintf(key, sizeof key, "AVION_VARIANT_%s", name);
+    const char* s = std::getenv(key);
+    return s ? std::atoi(s) : dflt;
+}
+
+// Workgroups are launched in multiples of 8 (one per XCD); the padding ones exit at once.
+bool grid_for(long long nblocks, unsigned* grid)
+{
+    const long long padded = ((nblocks + 7) / 8) * 8;
+    if (padded > 0x7fffffffLL) return false;
+    *grid = (unsigned)padded;
+    return true;
+}
+
+template <typename K>
+hipError_t allow_lds(K kernel, int bytes)
+{
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+}
+
+template <int D, int QT, int NW>
+int launch_fwd(const bf16* q, const bf16* k, const bf16* v, bf16* o, float* lse, int B, int H, int N, float scale,
+               hipStream_t st)
+{
+    using Cfg = FwdCfg<D, QT, NW>;
+    static hipError_t attr = allow_lds(avion_fwd_kernel<D, QT, NW>, Cfg::LDS_BYTES);
+    if (attr != hipSuccess) return hip_fail(attr, "hipFuncSetAttribute(fwd)");
+    const int nqb = (N + Cfg::BM - 1) / Cfg::BM;
+    const long long nblocks = (long long)nqb * B * H;
+    unsigned grid;
+    if (!grid_for(nblocks, &grid)) return AVION_EUNSUPPORTED;
+    hipLaunchKernelGGL((avion_fwd_kernel<D, QT, NW>), dim3(grid), dim3(Cfg::NT), Cfg::LDS_BYTES, st, q, k, v, o, lse, H,
+                       N, nqb, (int)nblocks, scale * kLog2e);
+    const hipError_t e = hipGetLastError();
+    return e == hipSuccess ? AVION_OK : hip_fail(e, "launch avion_fwd_kernel");
+}
+
+template <int D, int QT, int NW>
+int launch_dq(const bf16* q, const bf16* k, const bf16* v, const bf16* o, const bf16* dO, const float* lse, bf16* dq,
+              float* delta, int B, int H, int N, float scale, hipStream_t st)
+{
+    using Cfg = DqCfg<D, QT, NW>;
+    static hipError_t attr = allow_lds(avion_dq_kernel<D, QT, NW>, Cfg::LDS_BYTES);
+    if (attr != hipSuccess) return hip_fail(attr, "hipFuncSetAttribute(dq)");
+    const int nqb = (N + Cfg::BM - 1) / Cfg::BM;
+    const long long nblocks = (long long)nqb * B * H;
+    unsigned grid;
+    if (!grid_for(nblocks, &grid)) return AVION_EUNSUPPORTED;
+    hipLaunchKernelGGL((avion_dq_kernel<D, QT, NW>), dim3(grid), dim3(Cfg::NT), Cfg::LDS_BYTES, st, q, k, v, o, dO, lse,
+                       dq, delta, H, N, nqb, (int)nblocks, scale * kLog2e, scale);
+    const hipError_t e = hipGetLastError();
+    return e == hipSuccess ? AVION_OK : hip_fail(e, "launch avion_dq_kernel");
+}
+
+template <int D, int KT, int NW>
+int launch_dkdv(const bf16* q, const bf16* k, const bf16* v, const bf16* dO, const float* lse, const float* delta,
+                bf16* dk, bf16* dv, int B, int H, int N, float scale, hipStream_t st)
+{
+    using Cfg = DkvCfg<D, KT, NW>;
+    static hipError_t attr = allow_lds(avion_dkdv_kernel<D, KT, NW>, Cfg::LDS_BYTES);
+    if (attr != hipSuccess) return hip_fail(attr, "hipFuncSetAttribute(dkdv)");
+    const int nkb = (N + Cfg::BNK - 1) / Cfg::BNK;
+    const long long nblocks = (long long)nkb * B * H;
+    unsigned grid;
+    if (!grid_for(nblocks, &grid)) return AVION_EUNSUPPORTED;
+    hipLaunchKernelGGL((avion_dkdv_kernel<D, KT, NW>), dim3(grid), dim3(Cfg::NT), Cfg::LDS_BYTES, st, q, k, v, dO, lse,
+                       delta, dk, dv, H, N, nkb, (int)nblocks, scale * kLog2e, scale);
+    const hipError_t e = hipGetLastError();
+    return e == hipSuccess ? AVION_OK : hip_fail(e, "launch avion_dkdv_kernel");
+}
+
+template <int D>
+int fwd_dispatch(const bf16* q, const bf16* k, const bf16* v, bf16* o, float* lse, int B, int H, int N, float scale,
+                 hipStream_t st)
+{
+    static const int var = variant("FWD", 0);
+    switch (var) {
+        case 1: return launch_fwd<D, 1, 4>(q, k, v, o, lse, B, H, N, scale, st);
+        case 2: return launch_fwd<D, 2, 2>(q, k, v, o, lse, B, H, N, scale, st);
+        case 3: return launch_fwd<D, 1, 2>(q, k, v, o, lse, B, H, N, scale, st);
+        default: return launch_fwd<D, 2, 4>(q, k, v, o, lse, B, H, N, scale, st);
+    }
+}
+
+template <int D>
+int bwd_dispatch(const bf16* q, const bf16* k, const bf16* v, const bf16* o, const float* lse, const bf16* dO, bf16* dq,
+                 bf16* dk, bf16* dv, float* delta, int B, int H, int N, float scale, hipStream_t st)
+{
+    static const int vq = variant("DQ", 0);
+    static const int vk = variant("DKDV", 0);
+    int rc;
+    switch (vq) {
+        case 1: rc = launch_dq<D, 1, 4>(q, k, v, o, dO, lse, dq, delta, B, H, N, scale, st); break;
+        case 2: rc = launch_dq<D, 2, 2>(q, k, v, o, dO, lse, dq, delta, B, H, N, scale, st); break;
+        default: rc = launch_dq<D, 2, 4>(q, k, v, o, dO, lse, dq, delta, B, H, N, scale, st); break;
+    }
+    if (rc != AVION_OK) return rc;
+    switch (vk) {
+        case 1: return launch_dkdv<D, 1, 4>(q, k, v, dO, lse, delta, dk, dv, B, H, N, scale, st);
+        case 2: return launch_dkdv<D, 2, 2>(q, k, v, dO, lse, delta, dk, dv, B, H, N, scale, st);
+        case 3: return launch_dkdv<D, 1, 2>(q, k, v, dO, lse, delta, dk, dv, B, H, N, scale, st);
+        default: return launch_dkdv<D, 2, 4>(q, k, v, dO, lse, delta, dk, dv, B, H, N, scale, st);
+    }
+}
+
+}  // namespace
+
+extern "C" {
+
+int avion_version(void) { return 100; }
+
+const char* avion_strerror(int code)
+{
+    switch (code) {
+        case AVION_OK: return "ok";
+        case AVION_EINVAL: return "invalid argument (null pointer, B/H/N < 1, or scale not finite and positive)";
+        case AVION_EUNSUPPORTED: return "unsupported shape or alignment (d must be 64 or 80; pointers 16-byte aligned)";
+        case AVION_EWORKSPACE: return "workspace missing, misaligned or too small";
+        case AVION_EHIP: return "HIP runtime error (see avion_last_hip_error)";
+        default: return "unknown avion error code";
+    }
+}
+
+const char* avion_last_hip_error(void) { return g_hip_error; }
+
+int avion_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int N, int d,
+                   float scale, void* stream)
+{
+    if (!q || !k || !v || !o || !lse) return AVION_EINVAL;
+    const int rc = check_shape(B, H, N, d, scale);
+    if (rc != AVION_OK) return rc;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(lse)) return AVION_EUNSUPPORTED;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const bf16 *qq = static_cast<const bf16*>(q), *kk = static_cast<const bf16*>(k), *vv = static_cast<const bf16*>(v);
+    bf16* oo = static_cast<bf16*>(o);
+    if (d == 64) return fwd_dispatch<64>(qq, kk, vv, oo, lse, B, H, N, scale, st);
+    return fwd_dispatch<80>(qq, kk, vv, oo, lse, B, H, N, scale, st);
+}
+
+size_t avion_attn_bwd_workspace_bytes(int B, int H, int N, int d)
+{
+    if (check_shape(B, H, N, d, 1.0f) != AVION_OK) return 0;
+    const size_t bytes = (size_t)B * H * N * sizeof(float);
+    return (bytes + 255) & ~(size_t)255;
+}
+
+int avion_attn_bwd(const void* q, const void* k, const void* v, const void* o, const float* lse, const void* dO,
+                   void* dq, void* dk, void* dv, int B, int H, int N, int d, float scale, void* workspace,
+                   size_t workspace_bytes, void* stream)
+{
+    if (!q || !k || !v || !o || !lse || !dO || !dq || !dk || !dv) return AVION_EINVAL;
+    const int rc = check_shape(B, H, N, d, scale);
+    if (rc != AVION_OK) return rc;
+    const void* ptrs[] = {q, k, v, o, lse, dO, dq, dk, dv};
+    for (const void* p : ptrs)
+        if (!aligned16(p)) return AVION_EUNSUPPORTED;
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0 ||
+        workspace_bytes < avion_attn_bwd_workspace_bytes(B, H, N, d))
+        return AVION_EWORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    float* delta = static_cast<float*>(workspace);
+    const bf16 *qq = static_cast<const bf16*>(q), *kk = static_cast<const bf16*>(k), *vv = static_cast<const bf16*>(v),
+               *oo = static_cast<const bf16*>(o), *gg = static_cast<const bf16*>(dO);
+    bf16 *dqq = static_cast<bf16*>(dq), *dkk = static_cast<bf16*>(dk), *dvv = static_cast<bf16*>(dv);
+    if (d == 64) return bwd_dispatch<64>(qq, kk, vv, oo, lse, gg, dqq, dkk, dvv, delta, B, H, N, scale, st);
+    return bwd_dispatch<80>(qq, kk, vv, oo, lse, gg, dqq, dkk, dvv, delta, B, H, N, scale, st);
+}
+
+}  // extern "C"

@@ -1,0 +1,388 @@
+// Backward kernels.  P is rebuilt tile by tile from Q, K and the saved LSE, so no N x N matrix is
+// read or written (Sec. 3, "Flash Attention": the weights stay implicit; Sec. 4.1: the attention
+// activation memory disappears).  With s = scale*<q_i,k_j>, P = exp(s - LSE_i),
+// delta_i = sum_c dO_ic O_ic:
+//     dV = P^T dO ,  dP = dO V^T ,  dS = P o (dP - delta) ,  dQ = scale dS K ,  dK = scale dS^T Q.
+//
+// Two kernels, both free of atomics (results are bit-reproducible):
+//   avion_dq_kernel   : query-stationary.  Also computes delta from O and dO and saves it for the
+//                       second kernel.  Same shape as the forward: S^T = K Q^T and dP^T = V dO^T
+//                       land with lane = query, so LSE and delta are per-lane scalars and dS^T
+//                       feeds dQ^T = K^T dS^T as a B operand straight from registers.
+//   avion_dkdv_kernel : key-stationary.  S = Q K^T and dP = dO V^T land with lane = key, K and V
+//                       stay in registers as B operands, and P, dS feed dV^T = dO^T P and
+//                       dK^T = Q^T dS from registers; Q and dO tiles come through LDS both in
+//                       natural and in transposed form.
+// Each kernel recomputes S and dP for itself (7 contractions per tile pair instead of the
+// algorithmic 5); the extra two are not counted as useful work anywhere.
+#pragma once
+#include "avion_common.h"
+
+// --------------------------------------------------------------------------------------------- dQ
+template <int D, int QT, int NW>
+struct DqCfg {
+    static constexpr int BN = 64;
+    static constexpr int NT = NW * 64;
+    static constexpr int BM = 32 * QT * NW;
+    using NStage = NatStage<D, BN, NT>;
+    using TStage = TrStage<D, BN, NT>;
+    static constexpr int LDS_BYTES = 2 * (2 * NStage::BYTES + TStage::BYTES);
+};
+
+template <int D, int QT, int NW>
+__global__ void __launch_bounds__(NW * 64)
+avion_dq_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v,
+                const bf16* __restrict__ o, const bf16* __restrict__ dO, const float* __restrict__ lse,
+                bf16* __restrict__ dq, float* __restrict__ delta, int H, int N, int nqb, int nblocks,
+                float cs, float scale)
+{
+    using Cfg = DqCfg<D, QT, NW>;
+    using NStage = typename Cfg::NStage;
+    using TStage = typename Cfg::TStage;
+    constexpr int BN = Cfg::BN, BM = Cfg::BM;
+    constexpr int KS = D / 16;
+    constexpr int CT = (D + 31) / 32;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    // LDS: K tile buffers 0/1, V tile buffers 0/1, K^T tile buffers 0/1
+    auto kbuf = [&](int i) { return smem + i * NStage::BYTES; };
+    auto vbuf = [&](int i) { return smem + (2 + i) * NStage::BYTES; };
+    auto tbuf = [&](int i) { return smem + 4 * NStage::BYTES + i * TStage::BYTES; };
+
+    const int logical = xcd_local_id(blockIdx.x, nblocks);
+    if (logical < 0) return;
+    const int bh = logical / nqb, qb = logical % nqb;
+    const int b = bh / H, h = bh % H;
+    const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64, l32 = lane % 32, g = lane / 32;
+    const long rs = (long)H * D;
+    const long head_off = ((long)b * N * H + h) * D;
+    const bf16* kh = k + head_off;
+    const bf16* vh = v + head_off;
+    const int q0 = qb * BM + wave * 32 * QT;
+    const bool wave_active = q0 < N;
+
+    // Q and dO fragments (B operands), delta and LSE per lane
+    bf16x8 qf[QT][KS], gf[QT][KS];
+    float lc[QT], dl[QT];
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) {
+        const int row = min(q0 + 32 * qt + l32, N - 1);
+        const long off = head_off + (long)row * rs + g * 8;
+        float part = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            qf[qt][ks] = *reinterpret_cast<const bf16x8*>(q + off + ks * 16);
+            gf[qt][ks] = *reinterpret_cast<const bf16x8*>(dO + off + ks * 16);
+            const bf16x8 of = *reinterpret_cast<const bf16x8*>(o + off + ks * 16);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) part = fmaf((float)of[e], (float)gf[qt][ks][e], part);
+        }
+        dl[qt] = part + other_half(part);
+        lc[qt] = lse[(long)bh * N + row] * kLog2e;
+        if (wave_active && g == 0 && q0 + 32 * qt + l32 < N) delta[(long)bh * N + row] = dl[qt];
+    }
+
+    f32x16 acc[CT][QT];
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt)
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[ct][qt][i] = 0.f;
+
+    NStage kst, vst;
+    TStage tst;
+    TStage::zero_pad_rows(tbuf(0), tid);
+    TStage::zero_pad_rows(tbuf(1), tid);
+    kst.load(kh, rs, 0, N, tid);
+    vst.load(vh, rs, 0, N, tid);
+    tst.load(kh, rs, 0, N, tid);
+    kst.store(kbuf(0), tid);
+    vst.store(vbuf(0), tid);
+    tst.store(tbuf(0), tid);
+    __syncthreads();
+
+    const int ntiles = (N + BN - 1) / BN;
+    for (int t = 0; t < ntiles; ++t) {
+        const char* kc = kbuf(t & 1);
+        const char* vc = vbuf(t & 1);
+        const char* tc = tbuf(t & 1);
+        const bool more = t + 1 < ntiles;
+        if (more) {
+            kst.load(kh, rs, (t + 1) * BN, N, tid);
+            vst.load(vh, rs, (t + 1) * BN, N, tid);
+            tst.load(kh, rs, (t + 1) * BN, N, tid);
+        }
+        if (wave_active) {
+            const bool ragged = (t + 1) * BN > N;
+#pragma unroll
+            for (int kt = 0; kt < BN / 32; ++kt) {
+                f32x16 s[QT], dp[QT];
+#pragma unroll
+                for (int qt = 0; qt < QT; ++qt)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        s[qt][i] = 0.f;
+                        dp[qt][i] = 0.f;
+                    }
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    const bf16x8 ak = lds_frag(kc, NStage::STRIDE, 32 * kt + l32, ks, g);
+                    const bf16x8 av = lds_frag(vc, NStage::STRIDE, 32 * kt + l32, ks, g);
+#pragma unroll
+                    for (int qt = 0; qt < QT; ++qt) {
+                        s[qt] = mfma32(ak, qf[qt][ks], s[qt]);
+                        dp[qt] = mfma32(av, gf[qt][ks], dp[qt]);
+                    }
+                }
+                bf16x8 df[QT][2];
+#pragma unroll
+                for (int qt = 0; qt < QT; ++qt) {
+                    const float nl = -lc[qt];
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const float p = fast_exp2(fmaf(s[qt][i], cs, nl));
+                        s[qt][i] = p * (dp[qt][i] - dl[qt]);
+                    }
+                    // keys beyond N were staged as zero rows; force their dS to zero as well so
+                    // that an overflowing weight cannot turn 0 * inf into NaN
+                    if (ragged) {
+                        const int key0 = t * BN + 32 * kt + 4 * g;
+#pragma unroll
+                        for (int i = 0; i < 16; ++i)
+                            if (key0 + 8 * (i / 4) + (i % 4) >= N) s[qt][i] = 0.f;
+                    }
+                    df[qt][0] = acc_to_frag(s[qt], 0);
+                    df[qt][1] = acc_to_frag(s[qt], 1);
+                }
+#pragma unroll
+                for (int half = 0; half < 2; ++half)
+#pragma unroll
+                    for (int ct = 0; ct < CT; ++ct) {
+                        const bf16x8 a = lds_frag(tc, TStage::STRIDE, 32 * ct + l32, 2 * kt + half, g);
+#pragma unroll
+                        for (int qt = 0; qt < QT; ++qt) acc[ct][qt] = mfma32(a, df[qt][half], acc[ct][qt]);
+                    }
+            }
+        }
+        if (more) {
+            kst.store(kbuf((t + 1) & 1), tid);
+            vst.store(vbuf((t + 1) & 1), tid);
+            tst.store(tbuf((t + 1) & 1), tid);
+        }
+        __syncthreads();
+    }
+
+    if (!wave_active) return;
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) {
+        const int row = q0 + 32 * qt + l32;
+        if (row < N) {
+            bf16* drow = dq + head_off + (long)row * rs;
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+                for (int a4 = 0; a4 < 4; ++a4) {
+                    const int c0 = 32 * ct + 8 * a4 + 4 * g;
+                    if (c0 < D)
+                        store_bf16x4(drow + c0, acc[ct][qt][4 * a4 + 0] * scale, acc[ct][qt][4 * a4 + 1] * scale,
+                                     acc[ct][qt][4 * a4 + 2] * scale, acc[ct][qt][4 * a4 + 3] * scale);
+                }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------ dK, dV
+template <int D, int KT, int NW>
+struct DkvCfg {
+    static constexpr int BQ = 32;  // queries per LDS tile
+    static constexpr int NT = NW * 64;
+    static constexpr int BNK = 32 * KT * NW;  // keys per workgroup
+    using NStage = NatStage<D, BQ, NT>;
+    using TStage = TrStage<D, BQ, NT>;
+    static constexpr int ROWV_BYTES = 2 * BQ * 4;  // LSE*log2e and delta of the tile's queries
+    static constexpr int BUF_BYTES = 2 * NStage::BYTES + 2 * TStage::BYTES + ROWV_BYTES;
+    static constexpr int LDS_BYTES = 2 * BUF_BYTES;
+};
+
+template <int D, int KT, int NW>
+__global__ void __launch_bounds__(NW * 64)
+avion_dkdv_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v,
+                  const bf16* __restrict__ dO, const float* __restrict__ lse, const float* __restrict__ delta,
+                  bf16* __restrict__ dk, bf16* __restrict__ dv, int H, int N, int nkb, int nblocks,
+                  float cs, float scale)
+{
+    using Cfg = DkvCfg<D, KT, NW>;
+    using NStage = typename Cfg::NStage;
+    using TStage = typename Cfg::TStage;
+    constexpr int BQ = Cfg::BQ, BNK = Cfg::BNK;
+    constexpr int KS = D / 16;
+    constexpr int CT = (D + 31) / 32;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    // per buffer: Q natural | dO natural | Q transposed | dO transposed | lc[BQ] | dl[BQ]
+    constexpr int OFF_G = NStage::BYTES, OFF_QT = 2 * NStage::BYTES, OFF_GT = OFF_QT + TStage::BYTES,
+                  OFF_ROW = OFF_GT + TStage::BYTES;
+
+    const int logical = xcd_local_id(blockIdx.x, nblocks);
+    if (logical < 0) return;
+    const int bh = logical / nkb, kb = logical % nkb;
+    const int b = bh / H, h = bh % H;
+    const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64, l32 = lane % 32, g = lane / 32;
+    const long rs = (long)H * D;
+    const long head_off = ((long)b * N * H + h) * D;
+    const bf16* qh = q + head_off;
+    const bf16* gh = dO + head_off;
+    const float* lrow = lse + (long)bh * N;
+    const float* drow = delta + (long)bh * N;
+    const int k0 = kb * BNK + wave * 32 * KT;  // first key of this wavefront
+    const bool wave_active = k0 < N;
+
+    // K and V fragments (B operands: lane = key) stay in registers
+    bf16x8 kf[KT][KS], vf[KT][KS];
+#pragma unroll
+    for (int kt = 0; kt < KT; ++kt) {
+        const int row = min(k0 + 32 * kt + l32, N - 1);
+        const long off = head_off + (long)row * rs + g * 8;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            kf[kt][ks] = *reinterpret_cast<const bf16x8*>(k + off + ks * 16);
+            vf[kt][ks] = *reinterpret_cast<const bf16x8*>(v + off + ks * 16);
+        }
+    }
+
+    f32x16 dka[CT][KT], dva[CT][KT];
+#pragma unroll
+    for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                dka[ct][kt][i] = 0.f;
+                dva[ct][kt][i] = 0.f;
+            }
+
+    NStage qst, gst;
+    TStage qtst, gtst;
+    float lc_r = 0.f, dl_r = 0.f;
+    auto load_tile = [&](int r0) {
+        qst.load(qh, rs, r0, N, tid);
+        gst.load(gh, rs, r0, N, tid);
+        qtst.load(qh, rs, r0, N, tid);
+        gtst.load(gh, rs, r0, N, tid);
+        if (tid < BQ) {
+            const int tok = r0 + tid;
+            // queries beyond N get weight exp2(-inf) = 0, hence dS = 0 as well
+            lc_r = tok < N ? lrow[tok] * kLog2e : INFINITY;
+            dl_r = tok < N ? drow[tok] : 0.f;
+        }
+    };
+    auto store_tile = [&](char* buf) {
+        qst.store(buf, tid);
+        gst.store(buf + OFF_G, tid);
+        qtst.store(buf + OFF_QT, tid);
+        gtst.store(buf + OFF_GT, tid);
+        if (tid < BQ) {
+            reinterpret_cast<float*>(buf + OFF_ROW)[tid] = lc_r;
+            reinterpret_cast<float*>(buf + OFF_ROW)[BQ + tid] = dl_r;
+        }
+    };
+    for (int i = 0; i < 2; ++i) {
+        TStage::zero_pad_rows(smem + i * Cfg::BUF_BYTES + OFF_QT, tid);
+        TStage::zero_pad_rows(smem + i * Cfg::BUF_BYTES + OFF_GT, tid);
+    }
+    load_tile(0);
+    store_tile(smem);
+    __syncthreads();
+
+    const int ntiles = (N + BQ - 1) / BQ;
+    for (int t = 0; t < ntiles; ++t) {
+        const char* buf = smem + (t & 1) * Cfg::BUF_BYTES;
+        const bool more = t + 1 < ntiles;
+        if (more) load_tile((t + 1) * BQ);
+        if (wave_active) {
+#pragma unroll
+            for (int qt = 0; qt < BQ / 32; ++qt) {
+                // S and dP tiles: rows = 32 queries, cols = 32 keys
+                f32x16 s[KT], dp[KT];
+#pragma unroll
+                for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        s[kt][i] = 0.f;
+                        dp[kt][i] = 0.f;
+                    }
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    const bf16x8 aq = lds_frag(buf, NStage::STRIDE, 32 * qt + l32, ks, g);
+                    const bf16x8 ag = lds_frag(buf + OFF_G, NStage::STRIDE, 32 * qt + l32, ks, g);
+#pragma unroll
+                    for (int kt = 0; kt < KT; ++kt) {
+                        s[kt] = mfma32(aq, kf[kt][ks], s[kt]);
+                        dp[kt] = mfma32(ag, vf[kt][ks], dp[kt]);
+                    }
+                }
+                // per accumulator row (query): LSE*log2e and delta, broadcast reads from LDS
+                const float* rowv = reinterpret_cast<const float*>(buf + OFF_ROW) + 32 * qt + 4 * g;
+                bf16x8 pf[KT][2], df[KT][2];
+#pragma unroll
+                for (int a4 = 0; a4 < 4; ++a4) {
+                    const f32x4 l4 = *reinterpret_cast<const f32x4*>(rowv + 8 * a4);
+                    const f32x4 d4 = *reinterpret_cast<const f32x4*>(rowv + BQ + 8 * a4);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int i = 4 * a4 + e;
+#pragma unroll
+                        for (int kt = 0; kt < KT; ++kt) {
+                            const float p = fast_exp2(fmaf(s[kt][i], cs, -l4[e]));
+                            s[kt][i] = p;
+                            dp[kt][i] = p * (dp[kt][i] - d4[e]);
+                        }
+                    }
+                }
+#pragma unroll
+                for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+                    for (int half = 0; half < 2; ++half) {
+                        pf[kt][half] = acc_to_frag(s[kt], half);
+                        df[kt][half] = acc_to_frag(dp[kt], half);
+                    }
+                // dV^T += dO^T P ,  dK^T += Q^T dS   (contraction over the 32 queries, 2 steps)
+#pragma unroll
+                for (int half = 0; half < 2; ++half)
+#pragma unroll
+                    for (int ct = 0; ct < CT; ++ct) {
+                        const bf16x8 ag = lds_frag(buf + OFF_GT, TStage::STRIDE, 32 * ct + l32, 2 * qt + half, g);
+                        const bf16x8 aq = lds_frag(buf + OFF_QT, TStage::STRIDE, 32 * ct + l32, 2 * qt + half, g);
+#pragma unroll
+                        for (int kt = 0; kt < KT; ++kt) {
+                            dva[ct][kt] = mfma32(ag, pf[kt][half], dva[ct][kt]);
+                            dka[ct][kt] = mfma32(aq, df[kt][half], dka[ct][kt]);
+                        }
+                    }
+            }
+        }
+        if (more) store_tile(smem + ((t + 1) & 1) * Cfg::BUF_BYTES);
+        __syncthreads();
+    }
+
+    if (!wave_active) return;
+#pragma unroll
+    for (int kt = 0; kt < KT; ++kt) {
+        const int row = k0 + 32 * kt + l32;
+        if (row < N) {
+            bf16* dkrow = dk + head_off + (long)row * rs;
+            bf16* dvrow = dv + head_off + (long)row * rs;
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+                for (int a4 = 0; a4 < 4; ++a4) {
+                    const int c0 = 32 * ct + 8 * a4 + 4 * g;
+                    if (c0 < D) {
+                        store_bf16x4(dkrow + c0, dka[ct][kt][4 * a4 + 0] * scale, dka[ct][kt][4 * a4 + 1] * scale,
+                                     dka[ct][kt][4 * a4 + 2] * scale, dka[ct][kt][4 * a4 + 3] * scale);
+                        store_bf16x4(dvrow + c0, dva[ct][kt][4 * a4 + 0], dva[ct][kt][4 * a4 + 1],
+                                     dva[ct][kt][4 * a4 + 2], dva[ct][kt][4 * a4 + 3]);
+                    }
+                }
+        }
+    }
+}

@@ -1,0 +1,207 @@
+// Forward kernel: O = softmax(scale * Q K^T) V and LSE, one pass over the keys, nothing N x N stored
+// (Sec. 3, "Flash Attention": implicit softmax weights, block-wise work out of on-chip memory;
+// Sec. 1: block results combined into the exact output).
+//
+// Work split: one workgroup = NW wavefronts = 32*QT*NW consecutive queries of one (batch, head).
+// Each wavefront owns 32*QT queries and keeps, per query tile of 32:
+//   Q as MFMA B-operand fragments (lane = query, 8 channels per 16-deep step),
+//   O^T accumulators (lane = query, registers = channels), the running maximum and row sum.
+// Keys and values come in tiles of BN = 64 tokens through double-buffered LDS: K in its natural
+// row layout (A operand of S^T = K Q^T), V transposed (A operand of O^T = V^T P^T).
+// Computing the transposed products keeps every score of a query inside one lane pair, so the
+// accumulator of the first contraction is, after rounding to bf16, directly the B operand of the
+// second one (no LDS round trip), and the row maximum needs a single exchange between the two
+// halves of the wavefront.
+#pragma once
+#include "avion_common.h"
+
+// The stored maximum is only raised when the true maximum exceeds it by more than this many
+// binades; until then the weights are exp2 of at most kLazyBinades, well inside fp32/bf16 range,
+// and the final division by the row sum cancels the stale factor exactly.
+constexpr float kLazyBinades = 8.0f;
+
+template <int D, int QT, int NW>
+struct FwdCfg {
+    static constexpr int BN = 64;
+    static constexpr int NT = NW * 64;
+    static constexpr int BM = 32 * QT * NW;
+    using KStage = NatStage<D, BN, NT>;
+    using VStage = TrStage<D, BN, NT>;
+    static constexpr int LDS_BYTES = 2 * (KStage::BYTES + VStage::BYTES);
+};
+
+template <int D, int QT, int NW>
+__global__ void __launch_bounds__(NW * 64)
+avion_fwd_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v,
+                 bf16* __restrict__ o, float* __restrict__ lse, int H, int N, int nqb, int nblocks, float cs)
+{
+    using Cfg = FwdCfg<D, QT, NW>;
+    using KStage = typename Cfg::KStage;
+    using VStage = typename Cfg::VStage;
+    constexpr int BN = Cfg::BN, NT = Cfg::NT, BM = Cfg::BM;
+    constexpr int KS = D / 16;         // 16-deep steps over the channels
+    constexpr int CT = (D + 31) / 32;  // 32-channel tiles of O^T
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    // LDS: K tile buffers 0/1, then V^T tile buffers 0/1
+    auto kbuf = [&](int i) { return smem + i * KStage::BYTES; };
+    auto vbuf = [&](int i) { return smem + 2 * KStage::BYTES + i * VStage::BYTES; };
+
+    const int logical = xcd_local_id(blockIdx.x, nblocks);
+    if (logical < 0) return;
+    const int bh = logical / nqb, qb = logical % nqb;
+    const int b = bh / H, h = bh % H;
+    const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64, l32 = lane % 32, g = lane / 32;
+    const long rs = (long)H * D;
+    const long head_off = ((long)b * N * H + h) * D;
+    const bf16* qh = q + head_off;
+    const bf16* kh = k + head_off;
+    const bf16* vh = v + head_off;
+    bf16* oh = o + head_off;
+    const int q0 = qb * BM + wave * 32 * QT;  // first query of this wavefront
+    const bool wave_active = q0 < N;
+
+    // Q fragments stay in registers for the whole kernel
+    bf16x8 qf[QT][KS];
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) {
+        const int row = min(q0 + 32 * qt + l32, N - 1);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+            qf[qt][ks] = *reinterpret_cast<const bf16x8*>(qh + (long)row * rs + ks * 16 + g * 8);
+    }
+
+    f32x16 oacc[CT][QT];
+    float m_used[QT], lsum[QT], rsum[QT];
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) {
+        m_used[qt] = -INFINITY;
+        lsum[qt] = 0.f;
+        rsum[qt] = 0.f;
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) oacc[ct][qt][i] = 0.f;
+    }
+
+    KStage kst;
+    VStage vst;
+    VStage::zero_pad_rows(vbuf(0), tid);
+    VStage::zero_pad_rows(vbuf(1), tid);
+    kst.load(kh, rs, 0, N, tid);
+    vst.load(vh, rs, 0, N, tid);
+    kst.store(kbuf(0), tid);
+    vst.store(vbuf(0), tid);
+    __syncthreads();
+
+    const int ntiles = (N + BN - 1) / BN;
+    for (int t = 0; t < ntiles; ++t) {
+        const char* kc = kbuf(t & 1);
+        const char* vc = vbuf(t & 1);
+        const bool more = t + 1 < ntiles;
+        if (more) {
+            kst.load(kh, rs, (t + 1) * BN, N, tid);
+            vst.load(vh, rs, (t + 1) * BN, N, tid);
+        }
+        if (wave_active) {
+            const bool ragged = (t + 1) * BN > N;
+#pragma unroll
+            for (int kt = 0; kt < BN / 32; ++kt) {
+                // S^T tile: rows = 32 keys, cols = 32 queries
+                f32x16 s[QT];
+#pragma unroll
+                for (int qt = 0; qt < QT; ++qt)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) s[qt][i] = 0.f;
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    const bf16x8 a = lds_frag(kc, KStage::STRIDE, 32 * kt + l32, ks, g);
+#pragma unroll
+                    for (int qt = 0; qt < QT; ++qt) s[qt] = mfma32(a, qf[qt][ks], s[qt]);
+                }
+                if (ragged) {
+                    const int key0 = t * BN + 32 * kt + 4 * g;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int key = key0 + 8 * (i / 4) + (i % 4);
+                        if (key >= N) {
+#pragma unroll
+                            for (int qt = 0; qt < QT; ++qt) s[qt][i] = -INFINITY;
+                        }
+                    }
+                }
+                // online softmax in base 2: weights are exp2(cs*s - m_used)
+                bf16x8 pf[QT][2];
+#pragma unroll
+                for (int qt = 0; qt < QT; ++qt) {
+                    float mx = s[qt][0];
+#pragma unroll
+                    for (int i = 1; i < 16; ++i) mx = fmaxf(mx, s[qt][i]);
+                    mx = fmaxf(mx, other_half(mx));
+                    const float m2 = mx * cs;
+                    if (__builtin_amdgcn_ballot_w64(m2 > m_used[qt] + kLazyBinades) != 0ull) {
+                        const float mn = fmaxf(m_used[qt], m2);
+                        const float alpha = fast_exp2(m_used[qt] - mn);
+                        m_used[qt] = mn;
+                        lsum[qt] *= alpha;
+                        rsum[qt] *= alpha;
+#pragma unroll
+                        for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+                            for (int i = 0; i < 16; ++i) oacc[ct][qt][i] *= alpha;
+                    }
+                    const float nm = -m_used[qt];
+                    float rowsum = 0.f;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const float p = fast_exp2(fmaf(s[qt][i], cs, nm));
+                        s[qt][i] = p;
+                        rowsum += p;
+                    }
+                    lsum[qt] += rowsum;
+                    pf[qt][0] = acc_to_frag(s[qt], 0);
+                    pf[qt][1] = acc_to_frag(s[qt], 1);
+                    // Second row sum, over the weights as rounded to bf16, i.e. exactly the numbers
+                    // the second contraction multiplies V with.  O is divided by this one, which
+                    // makes it a true convex combination of value rows (the rounding of a dominant
+                    // weight cancels); LSE uses the unrounded sum.
+                    rsum[qt] = frag_sum(pf[qt][1], frag_sum(pf[qt][0], rsum[qt]));
+                }
+                // O^T += V^T P^T
+#pragma unroll
+                for (int half = 0; half < 2; ++half)
+#pragma unroll
+                    for (int ct = 0; ct < CT; ++ct) {
+                        const bf16x8 a = lds_frag(vc, VStage::STRIDE, 32 * ct + l32, 2 * kt + half, g);
+#pragma unroll
+                        for (int qt = 0; qt < QT; ++qt) oacc[ct][qt] = mfma32(a, pf[qt][half], oacc[ct][qt]);
+                    }
+            }
+        }
+        if (more) {
+            kst.store(kbuf((t + 1) & 1), tid);
+            vst.store(vbuf((t + 1) & 1), tid);
+        }
+        __syncthreads();
+    }
+
+    if (!wave_active) return;
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) {
+        const float l = lsum[qt] + other_half(lsum[qt]);
+        const float inv = 1.0f / (rsum[qt] + other_half(rsum[qt]));
+        const int row = q0 + 32 * qt + l32;
+        if (row < N) {
+            bf16* orow = oh + (long)row * rs;
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+                for (int a4 = 0; a4 < 4; ++a4) {
+                    const int c0 = 32 * ct + 8 * a4 + 4 * g;
+                    if (c0 < D)
+                        store_bf16x4(orow + c0, oacc[ct][qt][4 * a4 + 0] * inv, oacc[ct][qt][4 * a4 + 1] * inv,
+                                     oacc[ct][qt][4 * a4 + 2] * inv, oacc[ct][qt][4 * a4 + 3] * inv);
+                }
+            if (g == 0) lse[(long)bh * N + row] = (m_used[qt] + __builtin_amdgcn_logf(l)) * kLn2;
+        }
+    }
+}

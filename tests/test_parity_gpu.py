@@ -1,0 +1,131 @@
+"""GPU parity: the HIP kernels (through the C ABI) against the fp64 CPU oracle on the same seeded
+bf16 inputs.  Tolerances: max-abs <= 2e-2 and relative Frobenius <= 5e-3 for O, dQ, dK, dV;
+LSE within 1e-3 (see tests/gpu_harness.py)."""
+import numpy as np
+import pytest
+
+import synth_inputs as si
+from tests import gpu_harness as gh
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(w, slices=None, strict_abs=True):
+    x = si.make_inputs(w)
+    out = gh.run_hip(w, x)
+    rep = gh.check_against_oracle(w, x, out, slices, strict_abs)
+    worst = {k: f"{v[0]:.2e}/{v[1]:.2e}" for k, v in rep.items()}
+    print(f"\n{w.name}: shape={w.shape} errors(max-abs/rel-fro)={worst}", flush=True)
+    return x, out
+
+
+# sizes spanning several tiles with ragged tails, tiny N, and the CLS-token shapes (N+1)
+SMALL = [
+    # B, H,   N,  d
+    (1, 1, 1, 64), (1, 2, 2, 64), (2, 1, 31, 64), (1, 3, 33, 64), (1, 1, 63, 64), (2, 2, 64, 64),
+    (1, 2, 65, 64), (1, 1, 127, 64), (1, 2, 129, 64), (2, 3, 255, 64), (1, 2, 257, 64), (3, 5, 300, 64),
+    (1, 2, 785, 64), (1, 1, 784, 64), (1, 2, 513, 64),
+    (1, 1, 1, 80), (1, 2, 33, 80), (2, 2, 64, 80), (1, 3, 129, 80), (2, 2, 300, 80), (1, 1, 785, 80),
+]
+
+
+@pytest.mark.parametrize("B,H,N,d", SMALL)
+def test_small_shapes_match_oracle(B, H, N, d):
+    _run(si.small_workload(B, H, N, d, seed=1000 + 7 * N + d + B))
+
+
+def test_peaky_softmax_small():
+    # few effective keys: gradients reach magnitudes of 10 and more, so the absolute bound
+    # follows the bf16 ulp of the largest value; the relative bound is unchanged
+    _run(si.small_workload(2, 4, 333, 64, seed=4242, scale=0.125, k_mul=2.0), strict_abs=False)
+    _run(si.small_workload(1, 2, 200, 80, seed=4243, k_mul=4.0), strict_abs=False)
+
+
+def test_vitb_single_clip_full():
+    # configs[0]: every element of every output is compared
+    _run(si.WORKLOADS["vitb_clip"])
+
+
+def test_cls_token_shape_full_head_count():
+    # N = 1568 + 1 (a CLS token in front of the cubes), one clip
+    _run(si.small_workload(1, 12, 1569, 64, seed=99, scale=0.125))
+
+
+@pytest.mark.parametrize("name", ["vitb_batch", "vitl_batch_peaky", "vitb_long", "vith_d80", "vitl_336"])
+def test_full_size_configs_on_sampled_heads(name):
+    # The launch configuration bench.py times; the oracle recomputes whole (batch, head) slices
+    # (dK and dV of a head need every query of that head, so the head is the sampling unit).
+    w = si.WORKLOADS[name]
+    rng = np.random.default_rng(w.seed)
+    slices = {(0, 0), (w.B - 1, w.H - 1), (int(rng.integers(w.B)), int(rng.integers(w.H)))}
+    x, out = _run(w, sorted(slices))
+    # properties that hold at any size, on the whole tensors
+    import torch
+    for n in ("o", "dq", "dk", "dv", "lse"):
+        assert bool(torch.isfinite(out[n].float()).all()), n
+    # sum_j dV_j = sum_i dO_i per (b,h,c) (rows of P sum to one)
+    dv_sum = out["dv"].double().sum(1).cpu().numpy()
+    do_sum = si.bf16_bits_to_f64(x["dO"]).sum(1)
+    assert np.sqrt(((dv_sum - do_sum) ** 2).sum() / (do_sum ** 2).sum()) <= 2e-3
+
+
+def test_bitwise_reproducible():
+    import torch
+    w = si.small_workload(2, 3, 700, 64, seed=31337)
+    x = si.make_inputs(w)
+    a = gh.run_hip(w, x)
+    b = gh.run_hip(w, x)
+    for n in a:
+        assert torch.equal(a[n].view(torch.int16) if a[n].dtype == torch.bfloat16 else a[n],
+                           b[n].view(torch.int16) if b[n].dtype == torch.bfloat16 else b[n]), n
+
+
+def test_identical_keys_and_single_token_closed_forms_on_gpu():
+    # closed forms again, this time on the HIP path: identical keys -> O = mean of V
+    import torch
+    w = si.small_workload(1, 2, 150, 64, seed=5)
+    x = si.make_inputs(w)
+    x["k"][:] = x["k"][:, :1]
+    out = gh.run_hip(w, x)
+    v = si.bf16_bits_to_f64(x["v"])
+    o = gh.bf16_tensor_to_f64(out["o"])
+    assert np.abs(o - v.mean(1, keepdims=True)).max() < 3e-3
+    import oracle
+    ro, rl = oracle.fwd(x["q"], x["k"], x["v"], w.scale)
+    rdq, rdk, rdv = oracle.bwd(x["q"], x["k"], x["v"], x["dO"], w.scale)
+    gh.assert_close("O", o, ro)
+    assert np.abs(out["lse"].double().cpu().numpy() - rl).max() <= gh.LSE_ABS
+    gh.assert_close("dV", gh.bf16_tensor_to_f64(out["dv"]), rdv)
+    gh.assert_close("dK", gh.bf16_tensor_to_f64(out["dk"]), rdk)
+    # dQ is exactly zero here (every k_j is the same vector and rows of dS sum to zero):
+    # only an absolute bound makes sense
+    assert np.abs(rdq).max() < 1e-12
+    assert np.abs(gh.bf16_tensor_to_f64(out["dq"])).max() <= gh.MAX_ABS
+
+
+def test_large_magnitude_scores():
+    # scores around +-60 after scaling: exp() must not overflow, LSE must stay accurate
+    w = si.small_workload(1, 2, 130, 64, seed=77, scale=1.0)
+    x = si.make_inputs(w)
+    out = gh.run_hip(w, x)
+    import oracle
+    ro, rl = oracle.fwd(x["q"], x["k"], x["v"], w.scale)
+    o = gh.bf16_tensor_to_f64(out["o"])
+    assert np.all(np.isfinite(o))
+    assert np.abs(o - ro).max() <= 3e-2          # |O| is O(1) here (near one-hot weights)
+    assert np.abs(out["lse"].double().cpu().numpy() - rl).max() <= 2e-3 * np.abs(rl).max()
+
+
+def test_bad_arguments_raise_on_gpu_tensors():
+    import torch
+    import paper_2309_16669_amd as av
+    q = torch.zeros(1, 8, 2, 48, dtype=torch.bfloat16, device="cuda")
+    lse = torch.zeros(1, 2, 8, dtype=torch.float32, device="cuda")
+    with pytest.raises(av.AvionError) as e:
+        av.attn_fwd(q, q, q, torch.empty_like(q), lse, 0.1)
+    assert e.value.code == av.EUNSUPPORTED
+    q = torch.zeros(1, 8, 2, 64, dtype=torch.bfloat16, device="cuda")
+    ws = torch.empty(16, dtype=torch.uint8, device="cuda")
+    with pytest.raises(av.AvionError) as e:
+        av.attn_bwd(q, q, q, q, lse, q, torch.empty_like(q), torch.empty_like(q), torch.empty_like(q), 0.1, ws)
+    assert e.value.code == av.EWORKSPACE
