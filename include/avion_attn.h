@@ -21,8 +21,8 @@
  *   - Every tensor pointer must be 16-byte aligned.  Outputs must not alias inputs or each other.
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls only enqueue work
  *     on that stream and return; they never synchronise.
- *   - Supported head dims: d = 64 and d = 80.  Any B, H, N >= 1 with B*H <= 65535*... see
- *     AVION_EUNSUPPORTED below; N up to 2^24.
+ *   - Supported head dims: d = 64 and d = 80.  Any B, H, N >= 1 with N <= 2^24, B*H <= 2^24 and
+ *     fewer than 2^31 workgroups (see AVION_EUNSUPPORTED below).
  *   - Return value: AVION_OK (0) or a negative AVION_E* code.  On an argument error nothing is
  *     launched and no output is touched.  No exception crosses the boundary.
  *   - NaN/Inf in the inputs are not checked and propagate.
@@ -87,6 +87,27 @@ int avion_attn_bwd(const void *q, const void *k, const void *v, const void *o, c
                    const void *dO, void *dq, void *dk, void *dv,
                    int B, int H, int N, int d, float scale,
                    void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * The two phases of avion_attn_bwd, callable on their own (same argument rules as above).
+ * avion_attn_bwd(...) is exactly avion_attn_bwd_dq(...) followed by avion_attn_bwd_dkdv(...) on
+ * the same stream with the same workspace.
+ *
+ *   avion_attn_bwd_dq   : query-stationary pass.  Computes the row sums delta = rowsum(dO o O) into
+ *                         `workspace`, and dQ = scale * (P o (dO V^T - delta)) K.  Writes dq (fully)
+ *                         and the workspace.
+ *   avion_attn_bwd_dkdv : key-stationary pass.  Reads delta from `workspace` (as left there by
+ *                         avion_attn_bwd_dq for the same q, k, v, o, lse, dO) and computes
+ *                         dV = P^T dO and dK = scale * dS^T Q.  Writes dk, dv (fully).
+ * Both rebuild P from q, k and lse block by block (Sec. 3: the weights stay implicit).
+ */
+int avion_attn_bwd_dq(const void *q, const void *k, const void *v, const void *o, const float *lse,
+                      const void *dO, void *dq, int B, int H, int N, int d, float scale,
+                      void *workspace, size_t workspace_bytes, void *stream);
+
+int avion_attn_bwd_dkdv(const void *q, const void *k, const void *v, const float *lse,
+                        const void *dO, void *dk, void *dv, int B, int H, int N, int d, float scale,
+                        const void *workspace, size_t workspace_bytes, void *stream);
 
 #ifdef __cplusplus
 }

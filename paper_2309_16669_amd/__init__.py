@@ -47,6 +47,10 @@ def load_library() -> ctypes.CDLL:
         lib.avion_attn_bwd_workspace_bytes.argtypes = [i, i, i, i]
         lib.avion_attn_bwd.restype = i
         lib.avion_attn_bwd.argtypes = [p, p, p, p, p, p, p, p, p, i, i, i, i, f, p, sz, p]
+        lib.avion_attn_bwd_dq.restype = i
+        lib.avion_attn_bwd_dq.argtypes = [p, p, p, p, p, p, p, i, i, i, i, f, p, sz, p]
+        lib.avion_attn_bwd_dkdv.restype = i
+        lib.avion_attn_bwd_dkdv.argtypes = [p, p, p, p, p, p, p, i, i, i, i, f, p, sz, p]
         _lib = lib
     return _lib
 
@@ -116,3 +120,29 @@ def attn_bwd(q, k, v, o, lse, dO, dq, dk, dv, scale: float, workspace, stream=No
     _check(load_library().avion_attn_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(dO),
                                          _ptr(dq), _ptr(dk), _ptr(dv), B, H, N, d, float(scale),
                                          _ptr(workspace), workspace.numel(), _stream_handle(stream)))
+
+
+def attn_bwd_dq(q, k, v, o, lse, dO, dq, scale: float, workspace, stream=None) -> None:
+    """avion_attn_bwd_dq: first phase of the backward (delta into the workspace, and dQ)."""
+    import torch
+    B, N, H, d = q.shape
+    for t, n in ((q, "q"), (k, "k"), (v, "v"), (o, "o"), (dO, "dO"), (dq, "dq")):
+        _require(t, n, torch.bfloat16, (B, N, H, d))
+    _require(lse, "lse", torch.float32, (B, H, N))
+    _require(workspace, "workspace", torch.uint8)
+    _check(load_library().avion_attn_bwd_dq(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(dO), _ptr(dq),
+                                            B, H, N, d, float(scale), _ptr(workspace), workspace.numel(),
+                                            _stream_handle(stream)))
+
+
+def attn_bwd_dkdv(q, k, v, lse, dO, dk, dv, scale: float, workspace, stream=None) -> None:
+    """avion_attn_bwd_dkdv: second phase of the backward (dK, dV; reads delta from the workspace)."""
+    import torch
+    B, N, H, d = q.shape
+    for t, n in ((q, "q"), (k, "k"), (v, "v"), (dO, "dO"), (dk, "dk"), (dv, "dv")):
+        _require(t, n, torch.bfloat16, (B, N, H, d))
+    _require(lse, "lse", torch.float32, (B, H, N))
+    _require(workspace, "workspace", torch.uint8)
+    _check(load_library().avion_attn_bwd_dkdv(_ptr(q), _ptr(k), _ptr(v), _ptr(lse), _ptr(dO), _ptr(dk), _ptr(dv),
+                                              B, H, N, d, float(scale), _ptr(workspace), workspace.numel(),
+                                              _stream_handle(stream)))

@@ -123,24 +123,34 @@ int fwd_dispatch(const bf16* q, const bf16* k, const bf16* v, bf16* o, float* ls
 }
 
 template <int D>
-int bwd_dispatch(const bf16* q, const bf16* k, const bf16* v, const bf16* o, const float* lse, const bf16* dO, bf16* dq,
-                 bf16* dk, bf16* dv, float* delta, int B, int H, int N, float scale, hipStream_t st)
+int dq_dispatch(const bf16* q, const bf16* k, const bf16* v, const bf16* o, const float* lse, const bf16* dO, bf16* dq,
+                float* delta, int B, int H, int N, float scale, hipStream_t st)
 {
     static const int vq = variant("DQ", 0);
-    static const int vk = variant("DKDV", 0);
-    int rc;
     switch (vq) {
-        case 1: rc = launch_dq<D, 1, 4>(q, k, v, o, dO, lse, dq, delta, B, H, N, scale, st); break;
-        case 2: rc = launch_dq<D, 2, 2>(q, k, v, o, dO, lse, dq, delta, B, H, N, scale, st); break;
-        default: rc = launch_dq<D, 2, 4>(q, k, v, o, dO, lse, dq, delta, B, H, N, scale, st); break;
+        case 1: return launch_dq<D, 1, 4>(q, k, v, o, dO, lse, dq, delta, B, H, N, scale, st);
+        case 2: return launch_dq<D, 2, 2>(q, k, v, o, dO, lse, dq, delta, B, H, N, scale, st);
+        default: return launch_dq<D, 2, 4>(q, k, v, o, dO, lse, dq, delta, B, H, N, scale, st);
     }
-    if (rc != AVION_OK) return rc;
+}
+
+template <int D>
+int dkdv_dispatch(const bf16* q, const bf16* k, const bf16* v, const float* lse, const bf16* dO, bf16* dk, bf16* dv,
+                  const float* delta, int B, int H, int N, float scale, hipStream_t st)
+{
+    static const int vk = variant("DKDV", 0);
     switch (vk) {
         case 1: return launch_dkdv<D, 1, 4>(q, k, v, dO, lse, delta, dk, dv, B, H, N, scale, st);
         case 2: return launch_dkdv<D, 2, 2>(q, k, v, dO, lse, delta, dk, dv, B, H, N, scale, st);
         case 3: return launch_dkdv<D, 1, 2>(q, k, v, dO, lse, delta, dk, dv, B, H, N, scale, st);
         default: return launch_dkdv<D, 2, 4>(q, k, v, dO, lse, delta, dk, dv, B, H, N, scale, st);
     }
+}
+
+bool workspace_ok(const void* workspace, size_t workspace_bytes, int B, int H, int N, int d)
+{
+    return workspace && (reinterpret_cast<uintptr_t>(workspace) & 255u) == 0 &&
+           workspace_bytes >= avion_attn_bwd_workspace_bytes(B, H, N, d);
 }
 
 }  // namespace
@@ -184,26 +194,61 @@ size_t avion_attn_bwd_workspace_bytes(int B, int H, int N, int d)
     return (bytes + 255) & ~(size_t)255;
 }
 
+int avion_attn_bwd_dq(const void* q, const void* k, const void* v, const void* o, const float* lse, const void* dO,
+                      void* dq, int B, int H, int N, int d, float scale, void* workspace, size_t workspace_bytes,
+                      void* stream)
+{
+    if (!q || !k || !v || !o || !lse || !dO || !dq) return AVION_EINVAL;
+    const int rc = check_shape(B, H, N, d, scale);
+    if (rc != AVION_OK) return rc;
+    const void* ptrs[] = {q, k, v, o, lse, dO, dq};
+    for (const void* p : ptrs)
+        if (!aligned16(p)) return AVION_EUNSUPPORTED;
+    if (!workspace_ok(workspace, workspace_bytes, B, H, N, d)) return AVION_EWORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    float* delta = static_cast<float*>(workspace);
+    const bf16 *qq = static_cast<const bf16*>(q), *kk = static_cast<const bf16*>(k), *vv = static_cast<const bf16*>(v),
+               *oo = static_cast<const bf16*>(o), *gg = static_cast<const bf16*>(dO);
+    bf16* dqq = static_cast<bf16*>(dq);
+    if (d == 64) return dq_dispatch<64>(qq, kk, vv, oo, lse, gg, dqq, delta, B, H, N, scale, st);
+    return dq_dispatch<80>(qq, kk, vv, oo, lse, gg, dqq, delta, B, H, N, scale, st);
+}
+
+int avion_attn_bwd_dkdv(const void* q, const void* k, const void* v, const float* lse, const void* dO, void* dk,
+                        void* dv, int B, int H, int N, int d, float scale, const void* workspace,
+                        size_t workspace_bytes, void* stream)
+{
+    if (!q || !k || !v || !lse || !dO || !dk || !dv) return AVION_EINVAL;
+    const int rc = check_shape(B, H, N, d, scale);
+    if (rc != AVION_OK) return rc;
+    const void* ptrs[] = {q, k, v, lse, dO, dk, dv};
+    for (const void* p : ptrs)
+        if (!aligned16(p)) return AVION_EUNSUPPORTED;
+    if (!workspace_ok(workspace, workspace_bytes, B, H, N, d)) return AVION_EWORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const float* delta = static_cast<const float*>(workspace);
+    const bf16 *qq = static_cast<const bf16*>(q), *kk = static_cast<const bf16*>(k), *vv = static_cast<const bf16*>(v),
+               *gg = static_cast<const bf16*>(dO);
+    bf16 *dkk = static_cast<bf16*>(dk), *dvv = static_cast<bf16*>(dv);
+    if (d == 64) return dkdv_dispatch<64>(qq, kk, vv, lse, gg, dkk, dvv, delta, B, H, N, scale, st);
+    return dkdv_dispatch<80>(qq, kk, vv, lse, gg, dkk, dvv, delta, B, H, N, scale, st);
+}
+
 int avion_attn_bwd(const void* q, const void* k, const void* v, const void* o, const float* lse, const void* dO,
                    void* dq, void* dk, void* dv, int B, int H, int N, int d, float scale, void* workspace,
                    size_t workspace_bytes, void* stream)
 {
+    // every argument is checked before the first launch, so an error leaves all outputs untouched
     if (!q || !k || !v || !o || !lse || !dO || !dq || !dk || !dv) return AVION_EINVAL;
     const int rc = check_shape(B, H, N, d, scale);
     if (rc != AVION_OK) return rc;
     const void* ptrs[] = {q, k, v, o, lse, dO, dq, dk, dv};
     for (const void* p : ptrs)
         if (!aligned16(p)) return AVION_EUNSUPPORTED;
-    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0 ||
-        workspace_bytes < avion_attn_bwd_workspace_bytes(B, H, N, d))
-        return AVION_EWORKSPACE;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    float* delta = static_cast<float*>(workspace);
-    const bf16 *qq = static_cast<const bf16*>(q), *kk = static_cast<const bf16*>(k), *vv = static_cast<const bf16*>(v),
-               *oo = static_cast<const bf16*>(o), *gg = static_cast<const bf16*>(dO);
-    bf16 *dqq = static_cast<bf16*>(dq), *dkk = static_cast<bf16*>(dk), *dvv = static_cast<bf16*>(dv);
-    if (d == 64) return bwd_dispatch<64>(qq, kk, vv, oo, lse, gg, dqq, dkk, dvv, delta, B, H, N, scale, st);
-    return bwd_dispatch<80>(qq, kk, vv, oo, lse, gg, dqq, dkk, dvv, delta, B, H, N, scale, st);
+    if (!workspace_ok(workspace, workspace_bytes, B, H, N, d)) return AVION_EWORKSPACE;
+    const int rq = avion_attn_bwd_dq(q, k, v, o, lse, dO, dq, B, H, N, d, scale, workspace, workspace_bytes, stream);
+    if (rq != AVION_OK) return rq;
+    return avion_attn_bwd_dkdv(q, k, v, lse, dO, dk, dv, B, H, N, d, scale, workspace, workspace_bytes, stream);
 }
 
 }  // extern "C"
