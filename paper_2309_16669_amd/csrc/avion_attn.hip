@@ -31,6 +31,8 @@ int check_shape(int B, int H, int N, int d, float scale)
     if (!(scale > 0.f) || !std::isfinite(scale)) return AVION_EINVAL;
     if (d != 64 && d != 80) return AVION_EUNSUPPORTED;
     if (N > (1 << 24) || (long long)B * H > (1 << 24)) return AVION_EUNSUPPORTED;
+    // one (batch, head) slice is addressed with 32-bit byte offsets (buffer loads)
+    if ((long long)N * H * d * 2 >= (1LL << 31)) return AVION_EUNSUPPORTED;
     return AVION_OK;
 }
 

@@ -55,8 +55,8 @@ avion_dq_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf
     const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64, l32 = lane % 32, g = lane / 32;
     const long rs = (long)H * D;
     const long head_off = ((long)b * N * H + h) * D;
-    const bf16* kh = k + head_off;
-    const bf16* vh = v + head_off;
+    const SliceView kh(k + head_off, rs, N, D);
+    const SliceView vh(v + head_off, rs, N, D);
     const int q0 = qb * BM + wave * 32 * QT;
     const bool wave_active = q0 < N;
 
@@ -76,7 +76,7 @@ avion_dq_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf
 #pragma unroll
             for (int e = 0; e < 8; ++e) part = fmaf((float)of[e], (float)gf[qt][ks][e], part);
         }
-        dl[qt] = part + other_half(part);
+        dl[qt] = both_halves_sum(part);
         lc[qt] = lse[(long)bh * N + row] * kLog2e;
         if (wave_active && g == 0 && q0 + 32 * qt + l32 < N) delta[(long)bh * N + row] = dl[qt];
     }
@@ -93,9 +93,9 @@ avion_dq_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf
     TStage tst;
     TStage::zero_pad_rows(tbuf(0), tid);
     TStage::zero_pad_rows(tbuf(1), tid);
-    kst.load(kh, rs, 0, N, tid);
-    vst.load(vh, rs, 0, N, tid);
-    tst.load(kh, rs, 0, N, tid);
+    kst.load(kh, 0, tid);
+    vst.load(vh, 0, tid);
+    tst.load(kh, 0, tid);
     kst.store(kbuf(0), tid);
     vst.store(vbuf(0), tid);
     tst.store(tbuf(0), tid);
@@ -108,9 +108,9 @@ avion_dq_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf
         const char* tc = tbuf(t & 1);
         const bool more = t + 1 < ntiles;
         if (more) {
-            kst.load(kh, rs, (t + 1) * BN, N, tid);
-            vst.load(vh, rs, (t + 1) * BN, N, tid);
-            tst.load(kh, rs, (t + 1) * BN, N, tid);
+            kst.load(kh, (t + 1) * BN, tid);
+            vst.load(vh, (t + 1) * BN, tid);
+            tst.load(kh, (t + 1) * BN, tid);
         }
         if (wave_active) {
             const bool ragged = (t + 1) * BN > N;
@@ -126,8 +126,8 @@ avion_dq_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf
                     }
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
-                    const bf16x8 ak = lds_frag(kc, NStage::STRIDE, 32 * kt + l32, ks, g);
-                    const bf16x8 av = lds_frag(vc, NStage::STRIDE, 32 * kt + l32, ks, g);
+                    const bf16x8 ak = nat_frag(kc, NStage::STRIDE, 32 * kt + l32, ks, g);
+                    const bf16x8 av = nat_frag(vc, NStage::STRIDE, 32 * kt + l32, ks, g);
 #pragma unroll
                     for (int qt = 0; qt < QT; ++qt) {
                         s[qt] = mfma32(ak, qf[qt][ks], s[qt]);
@@ -158,7 +158,7 @@ avion_dq_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf
                 for (int half = 0; half < 2; ++half)
 #pragma unroll
                     for (int ct = 0; ct < CT; ++ct) {
-                        const bf16x8 a = lds_frag(tc, TStage::STRIDE, 32 * ct + l32, 2 * kt + half, g);
+                        const bf16x8 a = tr_frag(tc, TStage::STRIDE, 32 * ct + l32, 2 * kt + half, g);
 #pragma unroll
                         for (int qt = 0; qt < QT; ++qt) acc[ct][qt] = mfma32(a, df[qt][half], acc[ct][qt]);
                     }
@@ -229,8 +229,8 @@ avion_dkdv_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const 
     const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64, l32 = lane % 32, g = lane / 32;
     const long rs = (long)H * D;
     const long head_off = ((long)b * N * H + h) * D;
-    const bf16* qh = q + head_off;
-    const bf16* gh = dO + head_off;
+    const SliceView qh(q + head_off, rs, N, D);
+    const SliceView gh(dO + head_off, rs, N, D);
     const float* lrow = lse + (long)bh * N;
     const float* drow = delta + (long)bh * N;
     const int k0 = kb * BNK + wave * 32 * KT;  // first key of this wavefront
@@ -264,10 +264,10 @@ avion_dkdv_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const 
     TStage qtst, gtst;
     float lc_r = 0.f, dl_r = 0.f;
     auto load_tile = [&](int r0) {
-        qst.load(qh, rs, r0, N, tid);
-        gst.load(gh, rs, r0, N, tid);
-        qtst.load(qh, rs, r0, N, tid);
-        gtst.load(gh, rs, r0, N, tid);
+        qst.load(qh, r0, tid);
+        gst.load(gh, r0, tid);
+        qtst.load(qh, r0, tid);
+        gtst.load(gh, r0, tid);
         if (tid < BQ) {
             const int tok = r0 + tid;
             // queries beyond N get weight exp2(-inf) = 0, hence dS = 0 as well
@@ -312,8 +312,8 @@ avion_dkdv_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const 
                     }
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
-                    const bf16x8 aq = lds_frag(buf, NStage::STRIDE, 32 * qt + l32, ks, g);
-                    const bf16x8 ag = lds_frag(buf + OFF_G, NStage::STRIDE, 32 * qt + l32, ks, g);
+                    const bf16x8 aq = nat_frag(buf, NStage::STRIDE, 32 * qt + l32, ks, g);
+                    const bf16x8 ag = nat_frag(buf + OFF_G, NStage::STRIDE, 32 * qt + l32, ks, g);
 #pragma unroll
                     for (int kt = 0; kt < KT; ++kt) {
                         s[kt] = mfma32(aq, kf[kt][ks], s[kt]);
@@ -350,8 +350,8 @@ avion_dkdv_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const 
                 for (int half = 0; half < 2; ++half)
 #pragma unroll
                     for (int ct = 0; ct < CT; ++ct) {
-                        const bf16x8 ag = lds_frag(buf + OFF_GT, TStage::STRIDE, 32 * ct + l32, 2 * qt + half, g);
-                        const bf16x8 aq = lds_frag(buf + OFF_QT, TStage::STRIDE, 32 * ct + l32, 2 * qt + half, g);
+                        const bf16x8 ag = tr_frag(buf + OFF_GT, TStage::STRIDE, 32 * ct + l32, 2 * qt + half, g);
+                        const bf16x8 aq = tr_frag(buf + OFF_QT, TStage::STRIDE, 32 * ct + l32, 2 * qt + half, g);
 #pragma unroll
                         for (int kt = 0; kt < KT; ++kt) {
                             dva[ct][kt] = mfma32(ag, pf[kt][half], dva[ct][kt]);

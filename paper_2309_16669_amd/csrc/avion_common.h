@@ -17,8 +17,10 @@
 // Transposed LDS tile: one row per channel, R token slots of bf16 per row, stride R*2+16 bytes.
 //                      Token r of the tile sits at slot 16*(r/16) + 8*g + 4*a + e where
 //                      r%16 = 8*a + 4*g + e.  Lane group g of an MFMA then reads its 8 slots of
-//                      a 16-token step as one 16-byte word, and slot t = 4*a + e is the token that
+//                      a 16-token step as one 16-byte unit, and slot t = 4*a + e is the token that
 //                      accumulator register 8*step + t of the same lane group belongs to.
+//                      The 16-byte unit index within a row is XORed with (row/16)%4, which spreads
+//                      the 8-byte writes of the staging threads over all banks.
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -43,13 +45,54 @@ DEVINL f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c)
 
 DEVINL bf16x8 as_bf16x8(u32x4 x) { return __builtin_bit_cast(bf16x8, x); }
 
-// value held by the lane 32 away (the other half of the wavefront)
-DEVINL float other_half(float x)
+// max of three without the NaN-quieting moves the generic fmaxf lowering adds in front
+DEVINL float max3(float a, float b, float c)
 {
-    return __shfl_xor(x, 32, 64);
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+// Exchange between the two halves of the wavefront (lane l <-> lane l^32) with v_permlane32_swap.
+// The instruction swaps the upper half of its first register with the lower half of its second;
+// fed with two copies of x it leaves, in every lane, the lower-half lane's value in the first
+// result and the upper-half lane's value in the second.  The empty asm pins both results as
+// separate integer registers before they are reinterpreted as floats (without it this compiler
+// folds the two results into one register once they are bit-cast).
+DEVINL void halves(float x, float& lower, float& upper)
+{
+    const unsigned a = __builtin_bit_cast(unsigned, x);
+    const auto r = __builtin_amdgcn_permlane32_swap(a, a, false, false);
+    unsigned r0 = r[0], r1 = r[1];
+    asm volatile("" : "+v"(r0), "+v"(r1));
+    lower = __builtin_bit_cast(float, r0);
+    upper = __builtin_bit_cast(float, r1);
+}
+DEVINL float both_halves_max(float x)
+{
+    float lo, hi;
+    halves(x, lo, hi);
+    return max3(lo, hi, hi);
+}
+DEVINL float both_halves_sum(float x)
+{
+    float lo, hi;
+    halves(x, lo, hi);
+    return lo + hi;
 }
 
 DEVINL float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+DEVINL float max16(const f32x16& s)
+{
+    float m = max3(s[0], s[1], s[2]);
+    m = max3(m, s[3], s[4]);
+    m = max3(m, s[5], s[6]);
+    m = max3(m, s[7], s[8]);
+    m = max3(m, s[9], s[10]);
+    m = max3(m, s[11], s[12]);
+    m = max3(m, s[13], s[14]);
+    return max3(m, s[15], s[15]);
+}
 
 // two fp32 -> packed bf16 pair (round to nearest even), low half = a
 DEVINL unsigned pack_bf16(float a, float b)
@@ -86,16 +129,41 @@ DEVINL float frag_sum(bf16x8 f, float acc)
     return acc;
 }
 
-// 16-byte fragment of an LDS tile: row `row`, 16-deep step `step`, lane group g
-DEVINL bf16x8 lds_frag(const char* tile, int stride, int row, int step, int g)
+// ---------------------------------------------------------------------------------------------
+// Global memory view of one (batch, head) slice [N rows, row stride rs elements, D channels] as a
+// buffer resource: loads whose byte offset lies beyond the last row return zeros in hardware, so
+// tiles that hang over the end of the sequence need no branches.
+// ---------------------------------------------------------------------------------------------
+struct SliceView {
+    __amdgpu_buffer_rsrc_t rsrc;
+    unsigned row_bytes;  // rs * 2
+    DEVINL SliceView(const bf16* base, long rs, int N, int D)
+    {
+        const unsigned bytes = (unsigned)(((long)(N - 1) * rs + D) * 2);
+        rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16*>(base), 0, (int)bytes, 0x00020000);
+        row_bytes = (unsigned)(rs * 2);
+    }
+    DEVINL u32x4 load16(unsigned byte_off) const { return __builtin_amdgcn_raw_buffer_load_b128(rsrc, byte_off, 0, 0); }
+    DEVINL u32x2 load8(unsigned byte_off) const { return __builtin_amdgcn_raw_buffer_load_b64(rsrc, byte_off, 0, 0); }
+};
+constexpr unsigned kOutOfRange = 0x7fffffffu;  // a byte offset no slice reaches
+
+// 16-byte fragment of a natural LDS tile: row `row`, 16-deep step `step`, lane group g
+DEVINL bf16x8 nat_frag(const char* tile, int stride, int row, int step, int g)
 {
     return *reinterpret_cast<const bf16x8*>(tile + row * stride + step * 32 + g * 16);
+}
+// 16-byte fragment of a transposed LDS tile (unit index swizzled by the row)
+DEVINL bf16x8 tr_frag(const char* tile, int stride, int row, int step, int g)
+{
+    const int unit = (2 * step + g) ^ ((row >> 4) & 3);
+    return *reinterpret_cast<const bf16x8*>(tile + row * stride + unit * 16);
 }
 
 // ---------------------------------------------------------------------------------------------
 // Staging of a tile of R token rows x D channels from global memory into LDS through registers,
 // so that the global loads of the next tile are in flight while the current one is computed on.
-// Rows at or beyond N are filled with zeros.  NT = threads of the workgroup.
+// Rows at or beyond N come back as zeros.  NT = threads of the workgroup.
 // ---------------------------------------------------------------------------------------------
 template <int D, int R, int NT>
 struct NatStage {
@@ -106,16 +174,15 @@ struct NatStage {
     static constexpr int BYTES = R * STRIDE;
     u32x4 r[PER];
 
-    DEVINL void load(const bf16* base, long rs, int r0, int N, int tid)
+    DEVINL void load(const SliceView& src, int r0, int tid)
     {
 #pragma unroll
         for (int i = 0; i < PER; ++i) {
             const int idx = tid + i * NT;
             const int row = idx / CH, ch = idx % CH;
-            const int tok = r0 + row;
-            u32x4 val = {0u, 0u, 0u, 0u};
-            if (idx < TOTAL && tok < N) val = *reinterpret_cast<const u32x4*>(base + (long)tok * rs + ch * 8);
-            r[i] = val;
+            unsigned off = (unsigned)(r0 + row) * src.row_bytes + ch * 16;
+            if (TOTAL % NT != 0 && idx >= TOTAL) off = kOutOfRange;
+            r[i] = src.load16(off);
         }
     }
     DEVINL void store(char* tile, int tid) const
@@ -124,7 +191,7 @@ struct NatStage {
         for (int i = 0; i < PER; ++i) {
             const int idx = tid + i * NT;
             const int row = idx / CH, ch = idx % CH;
-            if (idx < TOTAL) *reinterpret_cast<u32x4*>(tile + row * STRIDE + ch * 16) = r[i];
+            if (TOTAL % NT == 0 || idx < TOTAL) *reinterpret_cast<u32x4*>(tile + row * STRIDE + ch * 16) = r[i];
         }
     }
 };
@@ -140,18 +207,26 @@ struct TrStage {
     static constexpr int BYTES = ROWS * STRIDE;
     u32x2 r[PER][4];
 
-    DEVINL void load(const bf16* base, long rs, int r0, int N, int tid)
+    // thread idx -> (channel quad, token quad); the two low bits of the token quad are swapped so
+    // that the 32 lanes of one LDS write phase land in distinct banks
+    DEVINL static void split(int idx, int& cq, int& tq)
+    {
+        cq = idx % CQ;
+        const int t = idx / CQ;
+        tq = (t & ~3) | ((t & 1) << 1) | ((t >> 1) & 1);
+    }
+    DEVINL void load(const SliceView& src, int r0, int tid)
     {
 #pragma unroll
         for (int i = 0; i < PER; ++i) {
             const int idx = tid + i * NT;
-            const int cq = idx % CQ, tq = idx / CQ;
+            int cq, tq;
+            split(idx, cq, tq);
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const int tok = r0 + 4 * tq + e;
-                u32x2 val = {0u, 0u};
-                if (idx < TOTAL && tok < N) val = *reinterpret_cast<const u32x2*>(base + (long)tok * rs + cq * 4);
-                r[i][e] = val;
+                unsigned off = (unsigned)(r0 + 4 * tq + e) * src.row_bytes + cq * 8;
+                if (TOTAL % NT != 0 && idx >= TOTAL) off = kOutOfRange;
+                r[i][e] = src.load8(off);
             }
         }
     }
@@ -161,10 +236,13 @@ struct TrStage {
 #pragma unroll
         for (int i = 0; i < PER; ++i) {
             const int idx = tid + i * NT;
-            const int cq = idx % CQ, tq = idx / CQ;
+            int cq, tq;
+            split(idx, cq, tq);
             const int grp = tq / 4, w4 = tq % 4;
             const int slot = 16 * grp + 8 * (w4 % 2) + 4 * (w4 / 2);
-            if (idx < TOTAL) {
+            const int unit = (slot >> 3) ^ ((cq >> 2) & 3);  // rows 4cq..4cq+3 share (row/16)%4
+            const int byte = unit * 16 + (slot & 7) * 2;
+            if (TOTAL % NT == 0 || idx < TOTAL) {
 #pragma unroll
                 for (int c = 0; c < 4; ++c) {
                     const int d = c / 2;
@@ -176,7 +254,7 @@ struct TrStage {
                         w[0] = (r[i][0][d] >> 16) | (r[i][1][d] & 0xffff0000u);
                         w[1] = (r[i][2][d] >> 16) | (r[i][3][d] & 0xffff0000u);
                     }
-                    *reinterpret_cast<u32x2*>(tile + (4 * cq + c) * STRIDE + slot * 2) = w;
+                    *reinterpret_cast<u32x2*>(tile + (4 * cq + c) * STRIDE + byte) = w;
                 }
             }
         }

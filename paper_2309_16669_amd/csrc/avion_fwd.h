@@ -54,8 +54,8 @@ avion_fwd_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const b
     const long rs = (long)H * D;
     const long head_off = ((long)b * N * H + h) * D;
     const bf16* qh = q + head_off;
-    const bf16* kh = k + head_off;
-    const bf16* vh = v + head_off;
+    const SliceView kh(k + head_off, rs, N, D);
+    const SliceView vh(v + head_off, rs, N, D);
     bf16* oh = o + head_off;
     const int q0 = qb * BM + wave * 32 * QT;  // first query of this wavefront
     const bool wave_active = q0 < N;
@@ -87,8 +87,8 @@ avion_fwd_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const b
     VStage vst;
     VStage::zero_pad_rows(vbuf(0), tid);
     VStage::zero_pad_rows(vbuf(1), tid);
-    kst.load(kh, rs, 0, N, tid);
-    vst.load(vh, rs, 0, N, tid);
+    kst.load(kh, 0, tid);
+    vst.load(vh, 0, tid);
     kst.store(kbuf(0), tid);
     vst.store(vbuf(0), tid);
     __syncthreads();
@@ -99,8 +99,8 @@ avion_fwd_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const b
         const char* vc = vbuf(t & 1);
         const bool more = t + 1 < ntiles;
         if (more) {
-            kst.load(kh, rs, (t + 1) * BN, N, tid);
-            vst.load(vh, rs, (t + 1) * BN, N, tid);
+            kst.load(kh, (t + 1) * BN, tid);
+            vst.load(vh, (t + 1) * BN, tid);
         }
         if (wave_active) {
             const bool ragged = (t + 1) * BN > N;
@@ -114,7 +114,7 @@ avion_fwd_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const b
                     for (int i = 0; i < 16; ++i) s[qt][i] = 0.f;
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
-                    const bf16x8 a = lds_frag(kc, KStage::STRIDE, 32 * kt + l32, ks, g);
+                    const bf16x8 a = nat_frag(kc, KStage::STRIDE, 32 * kt + l32, ks, g);
 #pragma unroll
                     for (int qt = 0; qt < QT; ++qt) s[qt] = mfma32(a, qf[qt][ks], s[qt]);
                 }
@@ -133,11 +133,7 @@ avion_fwd_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const b
                 bf16x8 pf[QT][2];
 #pragma unroll
                 for (int qt = 0; qt < QT; ++qt) {
-                    float mx = s[qt][0];
-#pragma unroll
-                    for (int i = 1; i < 16; ++i) mx = fmaxf(mx, s[qt][i]);
-                    mx = fmaxf(mx, other_half(mx));
-                    const float m2 = mx * cs;
+                    const float m2 = both_halves_max(max16(s[qt])) * cs;
                     if (__builtin_amdgcn_ballot_w64(m2 > m_used[qt] + kLazyBinades) != 0ull) {
                         const float mn = fmaxf(m_used[qt], m2);
                         const float alpha = fast_exp2(m_used[qt] - mn);
@@ -171,7 +167,7 @@ avion_fwd_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const b
                 for (int half = 0; half < 2; ++half)
 #pragma unroll
                     for (int ct = 0; ct < CT; ++ct) {
-                        const bf16x8 a = lds_frag(vc, VStage::STRIDE, 32 * ct + l32, 2 * kt + half, g);
+                        const bf16x8 a = tr_frag(vc, VStage::STRIDE, 32 * ct + l32, 2 * kt + half, g);
 #pragma unroll
                         for (int qt = 0; qt < QT; ++qt) oacc[ct][qt] = mfma32(a, pf[qt][half], oacc[ct][qt]);
                     }
@@ -187,8 +183,8 @@ avion_fwd_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const b
     if (!wave_active) return;
 #pragma unroll
     for (int qt = 0; qt < QT; ++qt) {
-        const float l = lsum[qt] + other_half(lsum[qt]);
-        const float inv = 1.0f / (rsum[qt] + other_half(rsum[qt]));
+        const float l = both_halves_sum(lsum[qt]);
+        const float inv = 1.0f / both_halves_sum(rsum[qt]);
         const int row = q0 + 32 * qt + l32;
         if (row < N) {
             bf16* orow = oh + (long)row * rs;
