@@ -8,11 +8,12 @@
 //   avion_dq_kernel   : query-stationary.  Also computes delta from O and dO and saves it for the
 //                       second kernel.  Same shape as the forward: S^T = K Q^T and dP^T = V dO^T
 //                       land with lane = query, so LSE and delta are per-lane scalars and dS^T
-//                       feeds dQ^T = K^T dS^T as a B operand straight from registers.
+//                       feeds dQ^T = K^T dS^T as a B operand straight from registers; K^T comes
+//                       from the same LDS tile as K, through transposing LDS loads.
 //   avion_dkdv_kernel : key-stationary.  S = Q K^T and dP = dO V^T land with lane = key, K and V
 //                       stay in registers as B operands, and P, dS feed dV^T = dO^T P and
-//                       dK^T = Q^T dS from registers; Q and dO tiles come through LDS both in
-//                       natural and in transposed form.
+//                       dK^T = Q^T dS from registers; the Q and dO tiles in LDS are read both as
+//                       rows and, through transposing LDS loads, as columns.
 // Each kernel recomputes S and dP for itself (7 contractions per tile pair instead of the
 // algorithmic 5); the extra two are not counted as useful work anywhere.
 #pragma once
@@ -24,9 +25,8 @@ struct DqCfg {
     static constexpr int BN = 64;
     static constexpr int NT = NW * 64;
     static constexpr int BM = 32 * QT * NW;
-    using NStage = NatStage<D, BN, NT>;
-    using TStage = TrStage<D, BN, NT>;
-    static constexpr int LDS_BYTES = 2 * (2 * NStage::BYTES + TStage::BYTES);
+    using Stage = TileStage<D, BN, NT>;
+    static constexpr int LDS_BYTES = 4 * Stage::BYTES;  // K0 K1 V0 V1
 };
 
 template <int D, int QT, int NW>
@@ -37,16 +37,13 @@ avion_dq_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf
                 float cs, float scale)
 {
     using Cfg = DqCfg<D, QT, NW>;
-    using NStage = typename Cfg::NStage;
-    using TStage = typename Cfg::TStage;
-    constexpr int BN = Cfg::BN, BM = Cfg::BM;
+    using Stage = typename Cfg::Stage;
+    constexpr int BN = Cfg::BN, BM = Cfg::BM, STRIDE = Stage::STRIDE;
     constexpr int KS = D / 16;
     constexpr int CT = (D + 31) / 32;
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    // LDS: K tile buffers 0/1, V tile buffers 0/1, K^T tile buffers 0/1
-    auto kbuf = [&](int i) { return smem + i * NStage::BYTES; };
-    auto vbuf = [&](int i) { return smem + (2 + i) * NStage::BYTES; };
-    auto tbuf = [&](int i) { return smem + 4 * NStage::BYTES + i * TStage::BYTES; };
+    auto kbuf = [&](int i) { return smem + i * Stage::BYTES; };
+    auto vbuf = [&](int i) { return smem + (2 + i) * Stage::BYTES; };
 
     const int logical = xcd_local_id(blockIdx.x, nblocks);
     if (logical < 0) return;
@@ -59,6 +56,7 @@ avion_dq_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf
     const SliceView vh(v + head_off, rs, N, D);
     const int q0 = qb * BM + wave * 32 * QT;
     const bool wave_active = q0 < N;
+    const int tr_off = tr_lane_offset(lane, STRIDE);
 
     // Q and dO fragments (B operands), delta and LSE per lane
     bf16x8 qf[QT][KS], gf[QT][KS];
@@ -85,32 +83,27 @@ avion_dq_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf
 #pragma unroll
     for (int qt = 0; qt < QT; ++qt)
 #pragma unroll
-        for (int ct = 0; ct < CT; ++ct)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[ct][qt][i] = 0.f;
+        for (int ct = 0; ct < CT; ++ct) acc[ct][qt] = f32x16_zero();
 
-    NStage kst, vst;
-    TStage tst;
-    TStage::zero_pad_rows(tbuf(0), tid);
-    TStage::zero_pad_rows(tbuf(1), tid);
+    Stage kst, vst;
+    if constexpr (D % 32 != 0) {
+        Stage::zero_pad(kbuf(0), tid);
+        Stage::zero_pad(kbuf(1), tid);
+    }
     kst.load(kh, 0, tid);
     vst.load(vh, 0, tid);
-    tst.load(kh, 0, tid);
     kst.store(kbuf(0), tid);
     vst.store(vbuf(0), tid);
-    tst.store(tbuf(0), tid);
     __syncthreads();
 
     const int ntiles = (N + BN - 1) / BN;
     for (int t = 0; t < ntiles; ++t) {
         const char* kc = kbuf(t & 1);
         const char* vc = vbuf(t & 1);
-        const char* tc = tbuf(t & 1);
         const bool more = t + 1 < ntiles;
         if (more) {
             kst.load(kh, (t + 1) * BN, tid);
             vst.load(vh, (t + 1) * BN, tid);
-            tst.load(kh, (t + 1) * BN, tid);
         }
         if (wave_active) {
             const bool ragged = (t + 1) * BN > N;
@@ -118,20 +111,13 @@ avion_dq_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf
             for (int kt = 0; kt < BN / 32; ++kt) {
                 f32x16 s[QT], dp[QT];
 #pragma unroll
-                for (int qt = 0; qt < QT; ++qt)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        s[qt][i] = 0.f;
-                        dp[qt][i] = 0.f;
-                    }
-#pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
-                    const bf16x8 ak = nat_frag(kc, NStage::STRIDE, 32 * kt + l32, ks, g);
-                    const bf16x8 av = nat_frag(vc, NStage::STRIDE, 32 * kt + l32, ks, g);
+                    const bf16x8 ak = nat_frag(kc, STRIDE, 32 * kt + l32, ks, g);
+                    const bf16x8 av = nat_frag(vc, STRIDE, 32 * kt + l32, ks, g);
 #pragma unroll
                     for (int qt = 0; qt < QT; ++qt) {
-                        s[qt] = mfma32(ak, qf[qt][ks], s[qt]);
-                        dp[qt] = mfma32(av, gf[qt][ks], dp[qt]);
+                        s[qt] = mfma32(ak, qf[qt][ks], ks == 0 ? f32x16_zero() : s[qt]);
+                        dp[qt] = mfma32(av, gf[qt][ks], ks == 0 ? f32x16_zero() : dp[qt]);
                     }
                 }
                 bf16x8 df[QT][2];
@@ -154,11 +140,12 @@ avion_dq_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf
                     df[qt][0] = acc_to_frag(s[qt], 0);
                     df[qt][1] = acc_to_frag(s[qt], 1);
                 }
+                // dQ^T += K^T dS^T
 #pragma unroll
                 for (int half = 0; half < 2; ++half)
 #pragma unroll
                     for (int ct = 0; ct < CT; ++ct) {
-                        const bf16x8 a = tr_frag(tc, TStage::STRIDE, 32 * ct + l32, 2 * kt + half, g);
+                        const bf16x8 a = tr_frag(kc, STRIDE, tr_off, ct, 2 * kt + half);
 #pragma unroll
                         for (int qt = 0; qt < QT; ++qt) acc[ct][qt] = mfma32(a, df[qt][half], acc[ct][qt]);
                     }
@@ -167,7 +154,6 @@ avion_dq_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf
         if (more) {
             kst.store(kbuf((t + 1) & 1), tid);
             vst.store(vbuf((t + 1) & 1), tid);
-            tst.store(tbuf((t + 1) & 1), tid);
         }
         __syncthreads();
     }
@@ -192,35 +178,32 @@ avion_dq_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf
 }
 
 // ------------------------------------------------------------------------------------------ dK, dV
-template <int D, int KT, int NW>
+template <int D, int KT, int NW, int BQ_ = 32>
 struct DkvCfg {
-    static constexpr int BQ = 32;  // queries per LDS tile
+    static constexpr int BQ = BQ_;  // queries per LDS tile
     static constexpr int NT = NW * 64;
     static constexpr int BNK = 32 * KT * NW;  // keys per workgroup
-    using NStage = NatStage<D, BQ, NT>;
-    using TStage = TrStage<D, BQ, NT>;
+    using Stage = TileStage<D, BQ, NT>;
     static constexpr int ROWV_BYTES = 2 * BQ * 4;  // LSE*log2e and delta of the tile's queries
-    static constexpr int BUF_BYTES = 2 * NStage::BYTES + 2 * TStage::BYTES + ROWV_BYTES;
+    static constexpr int BUF_BYTES = 2 * Stage::BYTES + ROWV_BYTES;
     static constexpr int LDS_BYTES = 2 * BUF_BYTES;
 };
 
-template <int D, int KT, int NW>
+template <int D, int KT, int NW, int BQ_>
 __global__ void __launch_bounds__(NW * 64)
 avion_dkdv_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v,
                   const bf16* __restrict__ dO, const float* __restrict__ lse, const float* __restrict__ delta,
                   bf16* __restrict__ dk, bf16* __restrict__ dv, int H, int N, int nkb, int nblocks,
                   float cs, float scale)
 {
-    using Cfg = DkvCfg<D, KT, NW>;
-    using NStage = typename Cfg::NStage;
-    using TStage = typename Cfg::TStage;
-    constexpr int BQ = Cfg::BQ, BNK = Cfg::BNK;
+    using Cfg = DkvCfg<D, KT, NW, BQ_>;
+    using Stage = typename Cfg::Stage;
+    constexpr int BQ = Cfg::BQ, BNK = Cfg::BNK, STRIDE = Stage::STRIDE;
     constexpr int KS = D / 16;
     constexpr int CT = (D + 31) / 32;
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    // per buffer: Q natural | dO natural | Q transposed | dO transposed | lc[BQ] | dl[BQ]
-    constexpr int OFF_G = NStage::BYTES, OFF_QT = 2 * NStage::BYTES, OFF_GT = OFF_QT + TStage::BYTES,
-                  OFF_ROW = OFF_GT + TStage::BYTES;
+    // per buffer: Q tile | dO tile | lc[BQ] | dl[BQ]
+    constexpr int OFF_G = Stage::BYTES, OFF_ROW = 2 * Stage::BYTES;
 
     const int logical = xcd_local_id(blockIdx.x, nblocks);
     if (logical < 0) return;
@@ -235,6 +218,7 @@ avion_dkdv_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const 
     const float* drow = delta + (long)bh * N;
     const int k0 = kb * BNK + wave * 32 * KT;  // first key of this wavefront
     const bool wave_active = k0 < N;
+    const int tr_off = tr_lane_offset(lane, STRIDE);
 
     // K and V fragments (B operands: lane = key) stay in registers
     bf16x8 kf[KT][KS], vf[KT][KS];
@@ -253,21 +237,16 @@ avion_dkdv_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const 
 #pragma unroll
     for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
-        for (int ct = 0; ct < CT; ++ct)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                dka[ct][kt][i] = 0.f;
-                dva[ct][kt][i] = 0.f;
-            }
+        for (int ct = 0; ct < CT; ++ct) {
+            dka[ct][kt] = f32x16_zero();
+            dva[ct][kt] = f32x16_zero();
+        }
 
-    NStage qst, gst;
-    TStage qtst, gtst;
+    Stage qst, gst;
     float lc_r = 0.f, dl_r = 0.f;
     auto load_tile = [&](int r0) {
         qst.load(qh, r0, tid);
         gst.load(gh, r0, tid);
-        qtst.load(qh, r0, tid);
-        gtst.load(gh, r0, tid);
         if (tid < BQ) {
             const int tok = r0 + tid;
             // queries beyond N get weight exp2(-inf) = 0, hence dS = 0 as well
@@ -278,16 +257,16 @@ avion_dkdv_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const 
     auto store_tile = [&](char* buf) {
         qst.store(buf, tid);
         gst.store(buf + OFF_G, tid);
-        qtst.store(buf + OFF_QT, tid);
-        gtst.store(buf + OFF_GT, tid);
         if (tid < BQ) {
             reinterpret_cast<float*>(buf + OFF_ROW)[tid] = lc_r;
             reinterpret_cast<float*>(buf + OFF_ROW)[BQ + tid] = dl_r;
         }
     };
-    for (int i = 0; i < 2; ++i) {
-        TStage::zero_pad_rows(smem + i * Cfg::BUF_BYTES + OFF_QT, tid);
-        TStage::zero_pad_rows(smem + i * Cfg::BUF_BYTES + OFF_GT, tid);
+    if constexpr (D % 32 != 0) {
+        for (int i = 0; i < 2; ++i) {
+            Stage::zero_pad(smem + i * Cfg::BUF_BYTES, tid);
+            Stage::zero_pad(smem + i * Cfg::BUF_BYTES + OFF_G, tid);
+        }
     }
     load_tile(0);
     store_tile(smem);
@@ -304,20 +283,13 @@ avion_dkdv_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const 
                 // S and dP tiles: rows = 32 queries, cols = 32 keys
                 f32x16 s[KT], dp[KT];
 #pragma unroll
-                for (int kt = 0; kt < KT; ++kt)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        s[kt][i] = 0.f;
-                        dp[kt][i] = 0.f;
-                    }
-#pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
-                    const bf16x8 aq = nat_frag(buf, NStage::STRIDE, 32 * qt + l32, ks, g);
-                    const bf16x8 ag = nat_frag(buf + OFF_G, NStage::STRIDE, 32 * qt + l32, ks, g);
+                    const bf16x8 aq = nat_frag(buf, STRIDE, 32 * qt + l32, ks, g);
+                    const bf16x8 ag = nat_frag(buf + OFF_G, STRIDE, 32 * qt + l32, ks, g);
 #pragma unroll
                     for (int kt = 0; kt < KT; ++kt) {
-                        s[kt] = mfma32(aq, kf[kt][ks], s[kt]);
-                        dp[kt] = mfma32(ag, vf[kt][ks], dp[kt]);
+                        s[kt] = mfma32(aq, kf[kt][ks], ks == 0 ? f32x16_zero() : s[kt]);
+                        dp[kt] = mfma32(ag, vf[kt][ks], ks == 0 ? f32x16_zero() : dp[kt]);
                     }
                 }
                 // per accumulator row (query): LSE*log2e and delta, broadcast reads from LDS
@@ -350,8 +322,8 @@ avion_dkdv_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const 
                 for (int half = 0; half < 2; ++half)
 #pragma unroll
                     for (int ct = 0; ct < CT; ++ct) {
-                        const bf16x8 ag = tr_frag(buf + OFF_GT, TStage::STRIDE, 32 * ct + l32, 2 * qt + half, g);
-                        const bf16x8 aq = tr_frag(buf + OFF_QT, TStage::STRIDE, 32 * ct + l32, 2 * qt + half, g);
+                        const bf16x8 ag = tr_frag(buf + OFF_G, STRIDE, tr_off, ct, 2 * qt + half);
+                        const bf16x8 aq = tr_frag(buf, STRIDE, tr_off, ct, 2 * qt + half);
 #pragma unroll
                         for (int kt = 0; kt < KT; ++kt) {
                             dva[ct][kt] = mfma32(ag, pf[kt][half], dva[ct][kt]);

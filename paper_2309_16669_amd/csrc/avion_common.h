@@ -12,15 +12,18 @@
 // rows (8 consecutive channels per lane), and operands whose contraction index is a token are read
 // from a transposed LDS tile whose token positions are permuted to match the accumulator rows.
 //
-// Natural LDS tile   : R token rows of D bf16, row stride D*2+16 bytes (the 16-byte pad makes the
-//                      16-byte fragment reads of 16 consecutive lanes hit distinct banks).
-// Transposed LDS tile: one row per channel, R token slots of bf16 per row, stride R*2+16 bytes.
-//                      Token r of the tile sits at slot 16*(r/16) + 8*g + 4*a + e where
-//                      r%16 = 8*a + 4*g + e.  Lane group g of an MFMA then reads its 8 slots of
-//                      a 16-token step as one 16-byte unit, and slot t = 4*a + e is the token that
-//                      accumulator register 8*step + t of the same lane group belongs to.
-//                      The 16-byte unit index within a row is XORed with (row/16)%4, which spreads
-//                      the 8-byte writes of the staging threads over all banks.
+// LDS tile: R token rows of D bf16 in their natural order, row stride D*2+16 bytes for D = 64 and
+// D*2+48 for D = 80 (an odd multiple of 16 bytes, so the 16-byte fragment reads of 16 consecutive
+// lanes hit distinct banks; for D = 80 the zeroed pad also covers the reads of the channel tile
+// that reaches past channel 79).
+//   natural fragment   : lane = token row, 8 consecutive channels -> one ds_read_b128.
+//   transposed fragment: lane = channel, 8 tokens.  Read from the same tile with two
+//                        ds_read_b64_tr_b16.  Within a group of 16 lanes that instruction hands
+//                        lane i, as element e, element i%4 of the 8 bytes addressed by lane
+//                        i/4 + 4e; lane j therefore addresses token 4g + j/4 (+8 for the second
+//                        read), channels c0 + 4(j%4).., and lane i receives channel c0 + i of
+//                        tokens 4g..4g+3, i.e. exactly the tokens that accumulator registers
+//                        8*step + 4a + e of lane group g belong to (a = 0 first read, 1 second).
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -34,6 +37,9 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((address_space(3))) char lds_char;
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
@@ -41,6 +47,12 @@ constexpr float kLn2 = 0.6931471805599453f;
 DEVINL f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c)
 {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+DEVINL f32x16 f32x16_zero()
+{
+    const f32x16 z = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    return z;
 }
 
 DEVINL bf16x8 as_bf16x8(u32x4 x) { return __builtin_bit_cast(bf16x8, x); }
@@ -148,16 +160,34 @@ struct SliceView {
 };
 constexpr unsigned kOutOfRange = 0x7fffffffu;  // a byte offset no slice reaches
 
-// 16-byte fragment of a natural LDS tile: row `row`, 16-deep step `step`, lane group g
+// row stride of an LDS tile in bytes
+template <int D>
+constexpr int tile_stride()
+{
+    return D == 64 ? 144 : D * 2 + 48;
+}
+
+// natural fragment: row `row`, 16-deep channel step `step`, lane group g
 DEVINL bf16x8 nat_frag(const char* tile, int stride, int row, int step, int g)
 {
     return *reinterpret_cast<const bf16x8*>(tile + row * stride + step * 32 + g * 16);
 }
-// 16-byte fragment of a transposed LDS tile (unit index swizzled by the row)
-DEVINL bf16x8 tr_frag(const char* tile, int stride, int row, int step, int g)
+
+// per-lane byte offset for transposed fragment reads (see the layout notes at the top)
+DEVINL int tr_lane_offset(int lane, int stride)
 {
-    const int unit = (2 * step + g) ^ ((row >> 4) & 3);
-    return *reinterpret_cast<const bf16x8*>(tile + row * stride + unit * 16);
+    const int G = lane >> 4, j = lane & 15;
+    return (4 * (G >> 1) + (j >> 2)) * stride + (16 * (G & 1) + 4 * (j & 3)) * 2;
+}
+// transposed fragment: channel tile ct (32 channels), 16-token step `step`
+DEVINL bf16x8 tr_frag(const char* tile, int stride, int lane_off, int ct, int step)
+{
+    const lds_char* p = (const lds_char*)tile + lane_off + step * 16 * stride + ct * 64;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)p);
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 8 * stride));
+    const u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
+    const u32x4 r = {l2[0], l2[1], h2[0], h2[1]};
+    return as_bf16x8(r);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -166,11 +196,11 @@ DEVINL bf16x8 tr_frag(const char* tile, int stride, int row, int step, int g)
 // Rows at or beyond N come back as zeros.  NT = threads of the workgroup.
 // ---------------------------------------------------------------------------------------------
 template <int D, int R, int NT>
-struct NatStage {
+struct TileStage {
     static constexpr int CH = D / 8;  // 16-byte chunks per row
     static constexpr int TOTAL = R * CH;
     static constexpr int PER = (TOTAL + NT - 1) / NT;
-    static constexpr int STRIDE = D * 2 + 16;
+    static constexpr int STRIDE = tile_stride<D>();
     static constexpr int BYTES = R * STRIDE;
     u32x4 r[PER];
 
@@ -194,78 +224,12 @@ struct NatStage {
             if (TOTAL % NT == 0 || idx < TOTAL) *reinterpret_cast<u32x4*>(tile + row * STRIDE + ch * 16) = r[i];
         }
     }
-};
-
-template <int D, int R, int NT>
-struct TrStage {
-    static constexpr int CQ = D / 4;  // channel quads
-    static constexpr int TQ = R / 4;  // token quads
-    static constexpr int TOTAL = CQ * TQ;
-    static constexpr int PER = (TOTAL + NT - 1) / NT;
-    static constexpr int STRIDE = R * 2 + 16;
-    static constexpr int ROWS = ((D + 31) / 32) * 32;  // channel rows incl. zero padding
-    static constexpr int BYTES = ROWS * STRIDE;
-    u32x2 r[PER][4];
-
-    // thread idx -> (channel quad, token quad); the two low bits of the token quad are swapped so
-    // that the 32 lanes of one LDS write phase land in distinct banks
-    DEVINL static void split(int idx, int& cq, int& tq)
+    // the pad of every row reads as zeros (only D = 80 ever reads it)
+    DEVINL static void zero_pad(char* tile, int tid)
     {
-        cq = idx % CQ;
-        const int t = idx / CQ;
-        tq = (t & ~3) | ((t & 1) << 1) | ((t >> 1) & 1);
-    }
-    DEVINL void load(const SliceView& src, int r0, int tid)
-    {
-#pragma unroll
-        for (int i = 0; i < PER; ++i) {
-            const int idx = tid + i * NT;
-            int cq, tq;
-            split(idx, cq, tq);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                unsigned off = (unsigned)(r0 + 4 * tq + e) * src.row_bytes + cq * 8;
-                if (TOTAL % NT != 0 && idx >= TOTAL) off = kOutOfRange;
-                r[i][e] = src.load8(off);
-            }
-        }
-    }
-    // 4x4 transpose of 16-bit values in registers, then four 8-byte LDS writes (one per channel)
-    DEVINL void store(char* tile, int tid) const
-    {
-#pragma unroll
-        for (int i = 0; i < PER; ++i) {
-            const int idx = tid + i * NT;
-            int cq, tq;
-            split(idx, cq, tq);
-            const int grp = tq / 4, w4 = tq % 4;
-            const int slot = 16 * grp + 8 * (w4 % 2) + 4 * (w4 / 2);
-            const int unit = (slot >> 3) ^ ((cq >> 2) & 3);  // rows 4cq..4cq+3 share (row/16)%4
-            const int byte = unit * 16 + (slot & 7) * 2;
-            if (TOTAL % NT == 0 || idx < TOTAL) {
-#pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    const int d = c / 2;
-                    u32x2 w;
-                    if (c % 2 == 0) {
-                        w[0] = (r[i][0][d] & 0xffffu) | (r[i][1][d] << 16);
-                        w[1] = (r[i][2][d] & 0xffffu) | (r[i][3][d] << 16);
-                    } else {
-                        w[0] = (r[i][0][d] >> 16) | (r[i][1][d] & 0xffff0000u);
-                        w[1] = (r[i][2][d] >> 16) | (r[i][3][d] & 0xffff0000u);
-                    }
-                    *reinterpret_cast<u32x2*>(tile + (4 * cq + c) * STRIDE + byte) = w;
-                }
-            }
-        }
-    }
-    // rows D..ROWS-1 (present when D is not a multiple of 32) must read as zeros
-    DEVINL static void zero_pad_rows(char* tile, int tid)
-    {
-        if constexpr (ROWS > D) {
-            constexpr int WORDS = (ROWS - D) * STRIDE / 4;
-            for (int i = tid; i < WORDS; i += NT) reinterpret_cast<unsigned*>(tile + D * STRIDE)[i] = 0u;
-        }
+        constexpr int PADW = (STRIDE - D * 2) / 4;
+        for (int i = tid; i < R * PADW; i += NT)
+            *reinterpret_cast<unsigned*>(tile + (i / PADW) * STRIDE + D * 2 + (i % PADW) * 4) = 0u;
     }
 };
 

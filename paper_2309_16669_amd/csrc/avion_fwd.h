@@ -5,9 +5,10 @@
 // Work split: one workgroup = NW wavefronts = 32*QT*NW consecutive queries of one (batch, head).
 // Each wavefront owns 32*QT queries and keeps, per query tile of 32:
 //   Q as MFMA B-operand fragments (lane = query, 8 channels per 16-deep step),
-//   O^T accumulators (lane = query, registers = channels), the running maximum and row sum.
-// Keys and values come in tiles of BN = 64 tokens through double-buffered LDS: K in its natural
-// row layout (A operand of S^T = K Q^T), V transposed (A operand of O^T = V^T P^T).
+//   O^T accumulators (lane = query, registers = channels), the running maximum and row sums.
+// Keys and values come in tiles of BN = 64 tokens through double-buffered LDS in their natural row
+// layout: K rows are the A operand of S^T = K Q^T, and V is read through transposing LDS loads as
+// the A operand of O^T = V^T P^T.
 // Computing the transposed products keeps every score of a query inside one lane pair, so the
 // accumulator of the first contraction is, after rounding to bf16, directly the B operand of the
 // second one (no LDS round trip), and the row maximum needs a single exchange between the two
@@ -25,9 +26,8 @@ struct FwdCfg {
     static constexpr int BN = 64;
     static constexpr int NT = NW * 64;
     static constexpr int BM = 32 * QT * NW;
-    using KStage = NatStage<D, BN, NT>;
-    using VStage = TrStage<D, BN, NT>;
-    static constexpr int LDS_BYTES = 2 * (KStage::BYTES + VStage::BYTES);
+    using Stage = TileStage<D, BN, NT>;
+    static constexpr int LDS_BYTES = 4 * Stage::BYTES;  // K0 K1 V0 V1
 };
 
 template <int D, int QT, int NW>
@@ -36,15 +36,13 @@ avion_fwd_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const b
                  bf16* __restrict__ o, float* __restrict__ lse, int H, int N, int nqb, int nblocks, float cs)
 {
     using Cfg = FwdCfg<D, QT, NW>;
-    using KStage = typename Cfg::KStage;
-    using VStage = typename Cfg::VStage;
-    constexpr int BN = Cfg::BN, NT = Cfg::NT, BM = Cfg::BM;
+    using Stage = typename Cfg::Stage;
+    constexpr int BN = Cfg::BN, BM = Cfg::BM, STRIDE = Stage::STRIDE;
     constexpr int KS = D / 16;         // 16-deep steps over the channels
     constexpr int CT = (D + 31) / 32;  // 32-channel tiles of O^T
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    // LDS: K tile buffers 0/1, then V^T tile buffers 0/1
-    auto kbuf = [&](int i) { return smem + i * KStage::BYTES; };
-    auto vbuf = [&](int i) { return smem + 2 * KStage::BYTES + i * VStage::BYTES; };
+    auto kbuf = [&](int i) { return smem + i * Stage::BYTES; };
+    auto vbuf = [&](int i) { return smem + (2 + i) * Stage::BYTES; };
 
     const int logical = xcd_local_id(blockIdx.x, nblocks);
     if (logical < 0) return;
@@ -59,6 +57,7 @@ avion_fwd_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const b
     bf16* oh = o + head_off;
     const int q0 = qb * BM + wave * 32 * QT;  // first query of this wavefront
     const bool wave_active = q0 < N;
+    const int tr_off = tr_lane_offset(lane, STRIDE);
 
     // Q fragments stay in registers for the whole kernel
     bf16x8 qf[QT][KS];
@@ -83,10 +82,11 @@ avion_fwd_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const b
             for (int i = 0; i < 16; ++i) oacc[ct][qt][i] = 0.f;
     }
 
-    KStage kst;
-    VStage vst;
-    VStage::zero_pad_rows(vbuf(0), tid);
-    VStage::zero_pad_rows(vbuf(1), tid);
+    Stage kst, vst;
+    if constexpr (D % 32 != 0) {
+        Stage::zero_pad(vbuf(0), tid);
+        Stage::zero_pad(vbuf(1), tid);
+    }
     kst.load(kh, 0, tid);
     vst.load(vh, 0, tid);
     kst.store(kbuf(0), tid);
@@ -109,14 +109,15 @@ avion_fwd_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const b
                 // S^T tile: rows = 32 keys, cols = 32 queries
                 f32x16 s[QT];
 #pragma unroll
-                for (int qt = 0; qt < QT; ++qt)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) s[qt][i] = 0.f;
-#pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
-                    const bf16x8 a = nat_frag(kc, KStage::STRIDE, 32 * kt + l32, ks, g);
+                    const bf16x8 a = nat_frag(kc, STRIDE, 32 * kt + l32, ks, g);
 #pragma unroll
-                    for (int qt = 0; qt < QT; ++qt) s[qt] = mfma32(a, qf[qt][ks], s[qt]);
+                    for (int qt = 0; qt < QT; ++qt) {
+                        if (ks == 0)
+                            s[qt] = mfma32(a, qf[qt][ks], f32x16_zero());
+                        else
+                            s[qt] = mfma32(a, qf[qt][ks], s[qt]);
+                    }
                 }
                 if (ragged) {
                     const int key0 = t * BN + 32 * kt + 4 * g;
@@ -167,7 +168,7 @@ avion_fwd_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const b
                 for (int half = 0; half < 2; ++half)
 #pragma unroll
                     for (int ct = 0; ct < CT; ++ct) {
-                        const bf16x8 a = tr_frag(vc, VStage::STRIDE, 32 * ct + l32, 2 * kt + half, g);
+                        const bf16x8 a = tr_frag(vc, STRIDE, tr_off, ct, 2 * kt + half);
 #pragma unroll
                         for (int qt = 0; qt < QT; ++qt) oacc[ct][qt] = mfma32(a, pf[qt][half], oacc[ct][qt]);
                     }
