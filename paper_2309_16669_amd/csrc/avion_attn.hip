@@ -94,18 +94,18 @@ int launch_dq(const bf16* q, const bf16* k, const bf16* v, const bf16* o, const 
     return e == hipSuccess ? AVION_OK : hip_fail(e, "launch avion_dq_kernel");
 }
 
-template <int D, int KT, int NW, int BQ>
+template <int D, int NW>
 int launch_dkdv(const bf16* q, const bf16* k, const bf16* v, const bf16* dO, const float* lse, const float* delta,
                 bf16* dk, bf16* dv, int B, int H, int N, float scale, hipStream_t st)
 {
-    using Cfg = DkvCfg<D, KT, NW, BQ>;
-    static hipError_t attr = allow_lds(avion_dkdv_kernel<D, KT, NW, BQ>, Cfg::LDS_BYTES);
+    using Cfg = DkvCfg<D, NW>;
+    static hipError_t attr = allow_lds(avion_dkdv_kernel<D, NW>, Cfg::LDS_BYTES);
     if (attr != hipSuccess) return hip_fail(attr, "hipFuncSetAttribute(dkdv)");
     const int nkb = (N + Cfg::BNK - 1) / Cfg::BNK;
     const long long nblocks = (long long)nkb * B * H;
     unsigned grid;
     if (!grid_for(nblocks, &grid)) return AVION_EUNSUPPORTED;
-    hipLaunchKernelGGL((avion_dkdv_kernel<D, KT, NW, BQ>), dim3(grid), dim3(Cfg::NT), Cfg::LDS_BYTES, st, q, k, v, dO, lse,
+    hipLaunchKernelGGL((avion_dkdv_kernel<D, NW>), dim3(grid), dim3(Cfg::NT), Cfg::LDS_BYTES, st, q, k, v, dO, lse,
                        delta, dk, dv, H, N, nkb, (int)nblocks, scale * kLog2e, scale);
     const hipError_t e = hipGetLastError();
     return e == hipSuccess ? AVION_OK : hip_fail(e, "launch avion_dkdv_kernel");
@@ -140,16 +140,11 @@ template <int D>
 int dkdv_dispatch(const bf16* q, const bf16* k, const bf16* v, const float* lse, const bf16* dO, bf16* dk, bf16* dv,
                   const float* delta, int B, int H, int N, float scale, hipStream_t st)
 {
-    static const int vk = variant("DKDV", 5);
+    static const int vk = variant("DKDV", 0);
     switch (vk) {
-        case 0: return launch_dkdv<D, 2, 4, 32>(q, k, v, dO, lse, delta, dk, dv, B, H, N, scale, st);
-        case 1: return launch_dkdv<D, 1, 4, 32>(q, k, v, dO, lse, delta, dk, dv, B, H, N, scale, st);
-        case 2: return launch_dkdv<D, 2, 2, 32>(q, k, v, dO, lse, delta, dk, dv, B, H, N, scale, st);
-        case 4: return launch_dkdv<D, 1, 2, 64>(q, k, v, dO, lse, delta, dk, dv, B, H, N, scale, st);
-        case 5: return launch_dkdv<D, 1, 4, 64>(q, k, v, dO, lse, delta, dk, dv, B, H, N, scale, st);
-        case 6: return launch_dkdv<D, 2, 2, 64>(q, k, v, dO, lse, delta, dk, dv, B, H, N, scale, st);
-        case 7: return launch_dkdv<D, 2, 4, 64>(q, k, v, dO, lse, delta, dk, dv, B, H, N, scale, st);
-        default: return launch_dkdv<D, 1, 2, 32>(q, k, v, dO, lse, delta, dk, dv, B, H, N, scale, st);
+        case 1: return launch_dkdv<D, 2>(q, k, v, dO, lse, delta, dk, dv, B, H, N, scale, st);
+        case 2: return launch_dkdv<D, 8>(q, k, v, dO, lse, delta, dk, dv, B, H, N, scale, st);
+        default: return launch_dkdv<D, 4>(q, k, v, dO, lse, delta, dk, dv, B, H, N, scale, st);
     }
 }
 

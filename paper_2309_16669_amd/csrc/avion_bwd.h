@@ -18,6 +18,9 @@
 // algorithmic 5); the extra two are not counted as useful work anywhere.
 #pragma once
 #include "avion_common.h"
+#ifndef AVION_ABL
+#define AVION_ABL 0
+#endif
 
 // --------------------------------------------------------------------------------------------- dQ
 template <int D, int QT, int NW>
@@ -97,6 +100,7 @@ avion_dq_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf
     __syncthreads();
 
     const int ntiles = (N + BN - 1) / BN;
+    wait_all_loads();
     for (int t = 0; t < ntiles; ++t) {
         const char* kc = kbuf(t & 1);
         const char* vc = vbuf(t & 1);
@@ -178,25 +182,34 @@ avion_dq_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf
 }
 
 // ------------------------------------------------------------------------------------------ dK, dV
-template <int D, int KT, int NW, int BQ_ = 32>
+// One wavefront owns 32 keys; the workgroup's NW wavefronts share LDS tiles of BQ = 64 queries
+// (Q and dO rows, LSE*log2e and delta), four buffers deep.  Work is cut into units of 32 queries.
+// In program order every unit holds three independent strands that the scheduler is asked to
+// interleave instruction by instruction, because a wavefront issues in order and an MFMA that is
+// queued behind another one blocks everything after it:
+//   matrix cores : S and dP of the NEXT unit (into a second accumulator pair), and the dV^T, dK^T
+//                  updates of the PREVIOUS unit (from its saved bf16 P and dS fragments);
+//   vector ALUs  : P = exp2(cs*S - lc), dS = P o (dP - delta) of the CURRENT unit, rounded to bf16.
+template <int D, int NW>
 struct DkvCfg {
-    static constexpr int BQ = BQ_;  // queries per LDS tile
+    static constexpr int BQ = 64;  // queries per LDS tile (two units)
     static constexpr int NT = NW * 64;
-    static constexpr int BNK = 32 * KT * NW;  // keys per workgroup
+    static constexpr int BNK = 32 * NW;  // keys per workgroup
+    static constexpr int NBUF = 4;
     using Stage = TileStage<D, BQ, NT>;
     static constexpr int ROWV_BYTES = 2 * BQ * 4;  // LSE*log2e and delta of the tile's queries
     static constexpr int BUF_BYTES = 2 * Stage::BYTES + ROWV_BYTES;
-    static constexpr int LDS_BYTES = 2 * BUF_BYTES;
+    static constexpr int LDS_BYTES = NBUF * BUF_BYTES;
 };
 
-template <int D, int KT, int NW, int BQ_>
+template <int D, int NW>
 __global__ void __launch_bounds__(NW * 64)
 avion_dkdv_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v,
                   const bf16* __restrict__ dO, const float* __restrict__ lse, const float* __restrict__ delta,
                   bf16* __restrict__ dk, bf16* __restrict__ dv, int H, int N, int nkb, int nblocks,
                   float cs, float scale)
 {
-    using Cfg = DkvCfg<D, KT, NW, BQ_>;
+    using Cfg = DkvCfg<D, NW>;
     using Stage = typename Cfg::Stage;
     constexpr int BQ = Cfg::BQ, BNK = Cfg::BNK, STRIDE = Stage::STRIDE;
     constexpr int KS = D / 16;
@@ -204,6 +217,7 @@ avion_dkdv_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const 
     extern __shared__ __attribute__((aligned(16))) char smem[];
     // per buffer: Q tile | dO tile | lc[BQ] | dl[BQ]
     constexpr int OFF_G = Stage::BYTES, OFF_ROW = 2 * Stage::BYTES;
+    auto tilebuf = [&](int ti) { return smem + (ti & 3) * Cfg::BUF_BYTES; };
 
     const int logical = xcd_local_id(blockIdx.x, nblocks);
     if (logical < 0) return;
@@ -216,31 +230,28 @@ avion_dkdv_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const 
     const SliceView gh(dO + head_off, rs, N, D);
     const float* lrow = lse + (long)bh * N;
     const float* drow = delta + (long)bh * N;
-    const int k0 = kb * BNK + wave * 32 * KT;  // first key of this wavefront
+    const int k0 = kb * BNK + wave * 32;  // first key of this wavefront
     const bool wave_active = k0 < N;
     const int tr_off = tr_lane_offset(lane, STRIDE);
 
     // K and V fragments (B operands: lane = key) stay in registers
-    bf16x8 kf[KT][KS], vf[KT][KS];
-#pragma unroll
-    for (int kt = 0; kt < KT; ++kt) {
-        const int row = min(k0 + 32 * kt + l32, N - 1);
+    bf16x8 kf[KS], vf[KS];
+    {
+        const int row = min(k0 + l32, N - 1);
         const long off = head_off + (long)row * rs + g * 8;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-            kf[kt][ks] = *reinterpret_cast<const bf16x8*>(k + off + ks * 16);
-            vf[kt][ks] = *reinterpret_cast<const bf16x8*>(v + off + ks * 16);
+            kf[ks] = *reinterpret_cast<const bf16x8*>(k + off + ks * 16);
+            vf[ks] = *reinterpret_cast<const bf16x8*>(v + off + ks * 16);
         }
     }
 
-    f32x16 dka[CT][KT], dva[CT][KT];
+    f32x16 dka[CT], dva[CT];
 #pragma unroll
-    for (int kt = 0; kt < KT; ++kt)
-#pragma unroll
-        for (int ct = 0; ct < CT; ++ct) {
-            dka[ct][kt] = f32x16_zero();
-            dva[ct][kt] = f32x16_zero();
-        }
+    for (int ct = 0; ct < CT; ++ct) {
+        dka[ct] = f32x16_zero();
+        dva[ct] = f32x16_zero();
+    }
 
     Stage qst, gst;
     float lc_r = 0.f, dl_r = 0.f;
@@ -263,84 +274,170 @@ avion_dkdv_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const 
         }
     };
     if constexpr (D % 32 != 0) {
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < Cfg::NBUF; ++i) {
             Stage::zero_pad(smem + i * Cfg::BUF_BYTES, tid);
             Stage::zero_pad(smem + i * Cfg::BUF_BYTES + OFF_G, tid);
         }
     }
+    const int ntiles = (N + BQ - 1) / BQ;
     load_tile(0);
-    store_tile(smem);
+    store_tile(tilebuf(0));
+    if (ntiles > 1) {
+        load_tile(BQ);
+        store_tile(tilebuf(1));
+    }
     __syncthreads();
 
-    const int ntiles = (N + BQ - 1) / BQ;
-    for (int t = 0; t < ntiles; ++t) {
-        const char* buf = smem + (t & 1) * Cfg::BUF_BYTES;
-        const bool more = t + 1 < ntiles;
-        if (more) load_tile((t + 1) * BQ);
-        if (wave_active) {
+    // S and dP of one unit: rows = 32 queries (half hq of the tile), cols = this wave's 32 keys
+    auto scores = [&](const char* buf, int hq, f32x16& s, f32x16& dp) {
 #pragma unroll
-            for (int qt = 0; qt < BQ / 32; ++qt) {
-                // S and dP tiles: rows = 32 queries, cols = 32 keys
-                f32x16 s[KT], dp[KT];
+        for (int ks = 0; ks < KS; ++ks) {
+            const bf16x8 aq = nat_frag(buf, STRIDE, 32 * hq + l32, ks, g);
+            const bf16x8 ag = nat_frag(buf + OFF_G, STRIDE, 32 * hq + l32, ks, g);
+            s = mfma32(aq, kf[ks], ks == 0 ? f32x16_zero() : s);
+            dp = mfma32(ag, vf[ks], ks == 0 ? f32x16_zero() : dp);
+        }
+    };
+    // dV^T += dO^T P ,  dK^T += Q^T dS  of one unit (contraction over its 32 queries, 2 steps)
+    auto accumulate = [&](const char* buf, int hq, const u32x4 (&pf)[2], const u32x4 (&df)[2]) {
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    const bf16x8 aq = nat_frag(buf, STRIDE, 32 * qt + l32, ks, g);
-                    const bf16x8 ag = nat_frag(buf + OFF_G, STRIDE, 32 * qt + l32, ks, g);
+        for (int half = 0; half < 2; ++half)
 #pragma unroll
-                    for (int kt = 0; kt < KT; ++kt) {
-                        s[kt] = mfma32(aq, kf[kt][ks], ks == 0 ? f32x16_zero() : s[kt]);
-                        dp[kt] = mfma32(ag, vf[kt][ks], ks == 0 ? f32x16_zero() : dp[kt]);
-                    }
-                }
-                // per accumulator row (query): LSE*log2e and delta, broadcast reads from LDS
-                const float* rowv = reinterpret_cast<const float*>(buf + OFF_ROW) + 32 * qt + 4 * g;
-                bf16x8 pf[KT][2], df[KT][2];
-#pragma unroll
-                for (int a4 = 0; a4 < 4; ++a4) {
-                    const f32x4 l4 = *reinterpret_cast<const f32x4*>(rowv + 8 * a4);
-                    const f32x4 d4 = *reinterpret_cast<const f32x4*>(rowv + BQ + 8 * a4);
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const int i = 4 * a4 + e;
-#pragma unroll
-                        for (int kt = 0; kt < KT; ++kt) {
-                            const float p = fast_exp2(fmaf(s[kt][i], cs, -l4[e]));
-                            s[kt][i] = p;
-                            dp[kt][i] = p * (dp[kt][i] - d4[e]);
-                        }
-                    }
-                }
-#pragma unroll
-                for (int kt = 0; kt < KT; ++kt)
-#pragma unroll
-                    for (int half = 0; half < 2; ++half) {
-                        pf[kt][half] = acc_to_frag(s[kt], half);
-                        df[kt][half] = acc_to_frag(dp[kt], half);
-                    }
-                // dV^T += dO^T P ,  dK^T += Q^T dS   (contraction over the 32 queries, 2 steps)
-#pragma unroll
-                for (int half = 0; half < 2; ++half)
-#pragma unroll
-                    for (int ct = 0; ct < CT; ++ct) {
-                        const bf16x8 ag = tr_frag(buf + OFF_G, STRIDE, tr_off, ct, 2 * qt + half);
-                        const bf16x8 aq = tr_frag(buf, STRIDE, tr_off, ct, 2 * qt + half);
-#pragma unroll
-                        for (int kt = 0; kt < KT; ++kt) {
-                            dva[ct][kt] = mfma32(ag, pf[kt][half], dva[ct][kt]);
-                            dka[ct][kt] = mfma32(aq, df[kt][half], dka[ct][kt]);
-                        }
-                    }
+            for (int ct = 0; ct < CT; ++ct) {
+                const bf16x8 ag = tr_frag(buf + OFF_G, STRIDE, tr_off, ct, 2 * hq + half);
+                const bf16x8 aq = tr_frag(buf, STRIDE, tr_off, ct, 2 * hq + half);
+                dva[ct] = mfma32(ag, as_bf16x8(pf[half]), dva[ct]);
+                dka[ct] = mfma32(aq, as_bf16x8(df[half]), dka[ct]);
+            }
+    };
+
+    // The MFMAs of one unit, in issue order: pairs (dV, dK) of the previous unit alternate with
+    // pairs (S, dP) of the next unit.  kind: 0 dV, 1 dK, 2 S, 3 dP; arg: half*CT+ct or ks.
+    constexpr int NA = 2 * CT, NB = KS, NM = 2 * (NA + NB);
+    struct Plan {
+        int kind[NM], arg[NM];
+    };
+    constexpr Plan plan = [] {
+        Plan p{};
+        int n = 0, ia = 0, ib = 0;
+        while (ia < NA || ib < NB) {
+            if (ia < NA) {
+                p.kind[n] = 0, p.arg[n++] = ia;
+                p.kind[n] = 1, p.arg[n++] = ia++;
+            }
+            if (ib < NB) {
+                p.kind[n] = 2, p.arg[n++] = ib;
+                p.kind[n] = 3, p.arg[n++] = ib++;
             }
         }
-        if (more) store_tile(smem + ((t + 1) & 1) * Cfg::BUF_BYTES);
+        return p;
+    }();
+    constexpr int LA = 3;  // LDS fragment reads run this many MFMAs ahead of their use
+
+    // One unit.  cur = S, dP of the current unit (turned into P, dS in place), nxt = accumulators of
+    // the next unit, *_p = bf16 fragments of the previous unit, *_c = those of the current one.
+    auto unit = [&](const char* bnext, int hnext, const char* bcur, int hcur, const char* bprev, int hprev,
+                    f32x16& s_c, f32x16& dp_c, f32x16& s_n, f32x16& dp_n, const u32x4 (&pf_p)[2],
+                    const u32x4 (&df_p)[2], u32x4 (&pf_c)[2], u32x4 (&df_c)[2]) {
+        auto frag = [&](int i) -> bf16x8 {
+            const int kd = plan.kind[i], ar = plan.arg[i];
+            if (kd == 0) return tr_frag(bprev + OFF_G, STRIDE, tr_off, ar % CT, 2 * hprev + ar / CT);
+            if (kd == 1) return tr_frag(bprev, STRIDE, tr_off, ar % CT, 2 * hprev + ar / CT);
+            if (kd == 2) return nat_frag(bnext, STRIDE, 32 * hnext + l32, ar, g);
+            return nat_frag(bnext + OFF_G, STRIDE, 32 * hnext + l32, ar, g);
+        };
+        const float* rowv = reinterpret_cast<const float*>(bcur + OFF_ROW) + 32 * hcur + 4 * g;
+        bf16x8 fr[NM];
+        f32x4 l4[4], d4[4];
+#pragma unroll
+        for (int i = 0; i < LA; ++i) fr[i] = frag(i);
+        l4[0] = *reinterpret_cast<const f32x4*>(rowv);
+        d4[0] = *reinterpret_cast<const f32x4*>(rowv + BQ);
+#pragma unroll
+        for (int i = 0; i < NM; ++i) {
+#if !(AVION_ABL & 4)
+            if (i + LA < NM) fr[i + LA] = frag(i + LA);
+#else
+            if (i + LA < NM) fr[i + LA] = fr[i % LA];
+#endif
+            const int kd = plan.kind[i], ar = plan.arg[i];
+#if !(AVION_ABL & 2)
+            if (kd == 0) dva[ar % CT] = mfma32(fr[i], as_bf16x8(pf_p[ar / CT]), dva[ar % CT]);
+            if (kd == 1) dka[ar % CT] = mfma32(fr[i], as_bf16x8(df_p[ar / CT]), dka[ar % CT]);
+            if (kd == 2) s_n = mfma32(fr[i], kf[ar], ar == 0 ? f32x16_zero() : s_n);
+            if (kd == 3) dp_n = mfma32(fr[i], vf[ar], ar == 0 ? f32x16_zero() : dp_n);
+#else
+            if (kd == 2 && ar == 0) s_n = f32x16_zero();
+            if (kd == 3 && ar == 0) dp_n = f32x16_zero();
+            if (kd >= 2) { s_n[ar] += (float)fr[i][0]; dp_n[ar] += (float)fr[i][1]; } else { dva[0][ar] += (float)fr[i][0]; }
+#endif
+            // vector-ALU share of this slot: elements e0..e1-1 of the current unit
+#if !(AVION_ABL & 1)
+            const int e0 = i * 16 / NM, e1 = (i + 1) * 16 / NM;
+#else
+            const int e0 = 0, e1 = 0;
+#endif
+#pragma unroll
+            for (int e = e0; e < e1; ++e) {
+                if (e % 4 == 0 && e + 4 < 16) {  // row values of the next four queries
+                    l4[e / 4 + 1] = *reinterpret_cast<const f32x4*>(rowv + 8 * (e / 4 + 1));
+                    d4[e / 4 + 1] = *reinterpret_cast<const f32x4*>(rowv + BQ + 8 * (e / 4 + 1));
+                }
+                const float pe = fast_exp2(fmaf(s_c[e], cs, -l4[e / 4][e % 4]));
+                s_c[e] = pe;
+                dp_c[e] = pe * (dp_c[e] - d4[e / 4][e % 4]);
+                if (e % 2 == 1) {
+                    pf_c[e / 8][(e / 2) % 4] = pack_bf16(s_c[e - 1], s_c[e]);
+                    df_c[e / 8][(e / 2) % 4] = pack_bf16(dp_c[e - 1], dp_c[e]);
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    f32x16 sA, dpA, sB, dpB;
+    u32x4 pfA[2], dfA[2], pfB[2], dfB[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const u32x4 z = {0u, 0u, 0u, 0u};
+        pfA[i] = z, dfA[i] = z, pfB[i] = z, dfB[i] = z;
+    }
+    if (wave_active) scores(tilebuf(0), 0, sA, dpA);
+    wait_all_loads();
+
+    for (int t = 0; t < ntiles; ++t) {
+#if !(AVION_ABL & 8)
+        if (t + 2 < ntiles) load_tile((t + 2) * BQ);
+#endif
+        if (wave_active) {
+            const char* bprev = tilebuf(t - 1 < 0 ? 0 : t - 1);
+            const char* bcur = tilebuf(t);
+            const char* bnext = tilebuf(t + 1);
+            __builtin_amdgcn_sched_barrier(0);
+            // unit 2t: current = A; next = unit 2t+1 (same tile, second half); previous = unit 2t-1
+            // (second half of tile t-1; at t = 0 its fragments are zero)
+            unit(bcur, 1, bcur, 0, bprev, 1, sA, dpA, sB, dpB, pfB, dfB, pfA, dfA);
+            // unit 2t+1: current = B; next = unit 2t+2 (first half of tile t+1; past the last tile
+            // this reads a stale buffer whose result is never used); previous = unit 2t
+            unit(bnext, 0, bcur, 1, bcur, 0, sB, dpB, sA, dpA, pfA, dfA, pfB, dfB);
+        }
+#if !(AVION_ABL & 8)
+        if (t + 2 < ntiles) store_tile(tilebuf(t + 2));
+#endif
+#if !(AVION_ABL & 16)
         __syncthreads();
+#endif
     }
 
     if (!wave_active) return;
-#pragma unroll
-    for (int kt = 0; kt < KT; ++kt) {
-        const int row = k0 + 32 * kt + l32;
+    accumulate(tilebuf(ntiles - 1), 1, pfB, dfB);  // the last unit's contribution
+    {
+        const int row = k0 + l32;
+#if (AVION_ABL & 32)
+        if (row < N && dka[0][0] == 12345.678f) {
+#else
         if (row < N) {
+#endif
             bf16* dkrow = dk + head_off + (long)row * rs;
             bf16* dvrow = dv + head_off + (long)row * rs;
 #pragma unroll
@@ -349,10 +446,10 @@ avion_dkdv_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const 
                 for (int a4 = 0; a4 < 4; ++a4) {
                     const int c0 = 32 * ct + 8 * a4 + 4 * g;
                     if (c0 < D) {
-                        store_bf16x4(dkrow + c0, dka[ct][kt][4 * a4 + 0] * scale, dka[ct][kt][4 * a4 + 1] * scale,
-                                     dka[ct][kt][4 * a4 + 2] * scale, dka[ct][kt][4 * a4 + 3] * scale);
-                        store_bf16x4(dvrow + c0, dva[ct][kt][4 * a4 + 0], dva[ct][kt][4 * a4 + 1],
-                                     dva[ct][kt][4 * a4 + 2], dva[ct][kt][4 * a4 + 3]);
+                        store_bf16x4(dkrow + c0, dka[ct][4 * a4 + 0] * scale, dka[ct][4 * a4 + 1] * scale,
+                                     dka[ct][4 * a4 + 2] * scale, dka[ct][4 * a4 + 3] * scale);
+                        store_bf16x4(dvrow + c0, dva[ct][4 * a4 + 0], dva[ct][4 * a4 + 1], dva[ct][4 * a4 + 2],
+                                     dva[ct][4 * a4 + 3]);
                     }
                 }
         }

@@ -92,6 +92,11 @@ DEVINL float both_halves_sum(float x)
     return lo + hi;
 }
 
+// Wait until every outstanding global/buffer load of this wavefront has returned (vmcnt(0)).
+// Placed once before a main loop so that loads issued in the prologue are not waited for again
+// inside the loop, where the same counter also covers the tile prefetch that should stay in flight.
+DEVINL void wait_all_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+
 DEVINL float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 DEVINL float max16(const f32x16& s)
