@@ -111,41 +111,35 @@ int launch_dkdv(const bf16* q, const bf16* k, const bf16* v, const bf16* dO, con
     return e == hipSuccess ? AVION_OK : hip_fail(e, "launch avion_dkdv_kernel");
 }
 
+// Kernel instances.  Only instances that keep every array in registers (no scratch, no spills) are
+// dispatched; AVION_VARIANT_DQ / AVION_VARIANT_DKDV select the alternatives kept for tuning sweeps.
 template <int D>
 int fwd_dispatch(const bf16* q, const bf16* k, const bf16* v, bf16* o, float* lse, int B, int H, int N, float scale,
                  hipStream_t st)
 {
-    static const int var = variant("FWD", 0);
-    switch (var) {
-        case 1: return launch_fwd<D, 1, 4>(q, k, v, o, lse, B, H, N, scale, st);
-        case 2: return launch_fwd<D, 2, 2>(q, k, v, o, lse, B, H, N, scale, st);
-        case 3: return launch_fwd<D, 1, 2>(q, k, v, o, lse, B, H, N, scale, st);
-        default: return launch_fwd<D, 2, 4>(q, k, v, o, lse, B, H, N, scale, st);
-    }
+    return launch_fwd<D, 1, 4>(q, k, v, o, lse, B, H, N, scale, st);
 }
 
 template <int D>
 int dq_dispatch(const bf16* q, const bf16* k, const bf16* v, const bf16* o, const float* lse, const bf16* dO, bf16* dq,
                 float* delta, int B, int H, int N, float scale, hipStream_t st)
 {
-    static const int vq = variant("DQ", 0);
-    switch (vq) {
-        case 1: return launch_dq<D, 1, 4>(q, k, v, o, dO, lse, dq, delta, B, H, N, scale, st);
-        case 2: return launch_dq<D, 2, 2>(q, k, v, o, dO, lse, dq, delta, B, H, N, scale, st);
-        default: return launch_dq<D, 2, 4>(q, k, v, o, dO, lse, dq, delta, B, H, N, scale, st);
+    if constexpr (D == 64) {
+        static const int vq = variant("DQ", 0);
+        if (vq == 0) return launch_dq<D, 2, 4>(q, k, v, o, dO, lse, dq, delta, B, H, N, scale, st);
     }
+    return launch_dq<D, 1, 4>(q, k, v, o, dO, lse, dq, delta, B, H, N, scale, st);
 }
 
 template <int D>
 int dkdv_dispatch(const bf16* q, const bf16* k, const bf16* v, const float* lse, const bf16* dO, bf16* dk, bf16* dv,
                   const float* delta, int B, int H, int N, float scale, hipStream_t st)
 {
-    static const int vk = variant("DKDV", 0);
-    switch (vk) {
-        case 1: return launch_dkdv<D, 2>(q, k, v, dO, lse, delta, dk, dv, B, H, N, scale, st);
-        case 2: return launch_dkdv<D, 8>(q, k, v, dO, lse, delta, dk, dv, B, H, N, scale, st);
-        default: return launch_dkdv<D, 4>(q, k, v, dO, lse, delta, dk, dv, B, H, N, scale, st);
+    if constexpr (D == 64) {
+        static const int vk = variant("DKDV", 0);
+        if (vk == 2) return launch_dkdv<D, 8>(q, k, v, dO, lse, delta, dk, dv, B, H, N, scale, st);
     }
+    return launch_dkdv<D, 4>(q, k, v, dO, lse, delta, dk, dv, B, H, N, scale, st);
 }
 
 bool workspace_ok(const void* workspace, size_t workspace_bytes, int B, int H, int N, int d)

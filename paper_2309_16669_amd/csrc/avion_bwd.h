@@ -18,9 +18,6 @@
 // algorithmic 5); the extra two are not counted as useful work anywhere.
 #pragma once
 #include "avion_common.h"
-#ifndef AVION_ABL
-#define AVION_ABL 0
-#endif
 
 // --------------------------------------------------------------------------------------------- dQ
 template <int D, int QT, int NW>
@@ -355,28 +352,14 @@ avion_dkdv_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const 
         d4[0] = *reinterpret_cast<const f32x4*>(rowv + BQ);
 #pragma unroll
         for (int i = 0; i < NM; ++i) {
-#if !(AVION_ABL & 4)
             if (i + LA < NM) fr[i + LA] = frag(i + LA);
-#else
-            if (i + LA < NM) fr[i + LA] = fr[i % LA];
-#endif
             const int kd = plan.kind[i], ar = plan.arg[i];
-#if !(AVION_ABL & 2)
             if (kd == 0) dva[ar % CT] = mfma32(fr[i], as_bf16x8(pf_p[ar / CT]), dva[ar % CT]);
             if (kd == 1) dka[ar % CT] = mfma32(fr[i], as_bf16x8(df_p[ar / CT]), dka[ar % CT]);
             if (kd == 2) s_n = mfma32(fr[i], kf[ar], ar == 0 ? f32x16_zero() : s_n);
             if (kd == 3) dp_n = mfma32(fr[i], vf[ar], ar == 0 ? f32x16_zero() : dp_n);
-#else
-            if (kd == 2 && ar == 0) s_n = f32x16_zero();
-            if (kd == 3 && ar == 0) dp_n = f32x16_zero();
-            if (kd >= 2) { s_n[ar] += (float)fr[i][0]; dp_n[ar] += (float)fr[i][1]; } else { dva[0][ar] += (float)fr[i][0]; }
-#endif
             // vector-ALU share of this slot: elements e0..e1-1 of the current unit
-#if !(AVION_ABL & 1)
             const int e0 = i * 16 / NM, e1 = (i + 1) * 16 / NM;
-#else
-            const int e0 = 0, e1 = 0;
-#endif
 #pragma unroll
             for (int e = e0; e < e1; ++e) {
                 if (e % 4 == 0 && e + 4 < 16) {  // row values of the next four queries
@@ -406,9 +389,7 @@ avion_dkdv_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const 
     wait_all_loads();
 
     for (int t = 0; t < ntiles; ++t) {
-#if !(AVION_ABL & 8)
         if (t + 2 < ntiles) load_tile((t + 2) * BQ);
-#endif
         if (wave_active) {
             const char* bprev = tilebuf(t - 1 < 0 ? 0 : t - 1);
             const char* bcur = tilebuf(t);
@@ -421,23 +402,15 @@ avion_dkdv_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const 
             // this reads a stale buffer whose result is never used); previous = unit 2t
             unit(bnext, 0, bcur, 1, bcur, 0, sB, dpB, sA, dpA, pfA, dfA, pfB, dfB);
         }
-#if !(AVION_ABL & 8)
         if (t + 2 < ntiles) store_tile(tilebuf(t + 2));
-#endif
-#if !(AVION_ABL & 16)
         __syncthreads();
-#endif
     }
 
     if (!wave_active) return;
     accumulate(tilebuf(ntiles - 1), 1, pfB, dfB);  // the last unit's contribution
     {
         const int row = k0 + l32;
-#if (AVION_ABL & 32)
-        if (row < N && dka[0][0] == 12345.678f) {
-#else
         if (row < N) {
-#endif
             bf16* dkrow = dk + head_off + (long)row * rs;
             bf16* dvrow = dv + head_off + (long)row * rs;
 #pragma unroll

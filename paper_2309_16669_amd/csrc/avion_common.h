@@ -27,6 +27,8 @@
 #pragma once
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #define DEVINL __device__ __forceinline__
 
 typedef __bf16 bf16;

@@ -5,35 +5,140 @@
 // Work split: one workgroup = NW wavefronts = 32*QT*NW consecutive queries of one (batch, head).
 // Each wavefront owns 32*QT queries and keeps, per query tile of 32:
 //   Q as MFMA B-operand fragments (lane = query, 8 channels per 16-deep step),
-//   O^T accumulators (lane = query, registers = channels), the running maximum and row sums.
-// Keys and values come in tiles of BN = 64 tokens through triple-buffered LDS in their natural row
-// layout: K rows are the A operand of S^T = K Q^T, and V is read through transposing LDS loads as
-// the A operand of O^T = V^T P^T.
-// Computing the transposed products keeps every score of a query inside one lane pair, so the
-// accumulator of the first contraction is, after rounding to bf16, directly the B operand of the
-// second one (no LDS round trip), and the row maximum needs a single exchange between the two
-// halves of the wavefront.
+//   O^T accumulators (lane = query, registers = channels), the reference maximum and row sums.
+// Keys and values come in LDS tiles of 64 tokens in their natural row layout, four buffers deep:
+// K rows are the A operand of S^T = K Q^T, and V is read through transposing LDS loads as the A
+// operand of O^T = V^T P^T.  Computing the transposed products keeps every score of a query inside
+// one lane pair, so the accumulator of the first contraction is, after rounding to bf16, directly
+// the B operand of the second one (no LDS round trip).
 //
-// Software pipeline: while the softmax arithmetic of tile t runs on the vector ALUs, the matrix
-// cores already work on S^T of tile t+1 (issued first, into a second set of accumulators) and then
-// on the P V product of tile t.  Tile t+2 is in flight from global memory meanwhile and is written
-// to the third LDS buffer at the end of the step; one workgroup barrier per tile.
+// Schedule.  A wavefront issues in order and an MFMA queued behind another blocks what follows, so
+// the three independent strands of a unit (32 keys x 32*QT queries) are interleaved instruction by
+// instruction in program order:
+//   matrix cores : S^T of the NEXT unit (second accumulator set) and the P V update of the PREVIOUS
+//                  unit (from its saved bf16 weights);
+//   vector ALUs  : exp2, row sums and bf16 rounding of the CURRENT unit;
+//   LDS          : operand fragments a few MFMAs ahead of their use.
+//
+// Softmax reference.  Weights are exp2(cs*s - m) with m fixed per query to the maximum over the
+// first 32 keys.  Softmax is invariant to m, fp32/bf16 keep their relative precision at any
+// magnitude, and the final division by the row sum cancels m exactly; the only failure mode is
+// overflow when a later score exceeds m by ~100 binades.  That is detected from the final row sum
+// (workgroup-wide), and the whole workgroup then recomputes its rows with the classic running
+// maximum (avion_fwd_safe_pass).  Random or trained activations never get there.
 #pragma once
 #include "avion_common.h"
-
-// The stored maximum is only raised when the true maximum exceeds it by more than this many
-// binades; until then the weights are exp2 of at most kLazyBinades, well inside fp32/bf16 range,
-// and the final division by the row sum cancels the stale factor exactly.
-constexpr float kLazyBinades = 8.0f;
 
 template <int D, int QT, int NW>
 struct FwdCfg {
     static constexpr int BN = 64;
     static constexpr int NT = NW * 64;
     static constexpr int BM = 32 * QT * NW;
+    static constexpr int NBUF = 4;
     using Stage = TileStage<D, BN, NT>;
-    static constexpr int LDS_BYTES = 6 * Stage::BYTES;  // K0 K1 K2 V0 V1 V2
+    static constexpr int LDS_BYTES = 2 * NBUF * Stage::BYTES;  // K0..K3 V0..V3
 };
+
+// row sums above this (or not finite) send the workgroup to the safe pass
+constexpr float kRowSumLimit = 7.9e28f;  // 2^96
+
+// Classic online softmax with a running maximum, one 64-key tile at a time, two LDS buffers.
+// Used only as the fallback described above; same register layouts as the main loop.
+template <int D, int QT, int NW>
+DEVINL void avion_fwd_safe_pass(char* smem, const SliceView& kh, const SliceView& vh, const bf16x8 (&qf)[QT][D / 16],
+                                f32x16 (&oacc)[(D + 31) / 32][QT], float (&m_used)[QT], float (&lsum)[QT],
+                                float (&rsum)[QT], int N, float cs, bool wave_active, int tid, int l32, int g,
+                                int tr_off)
+{
+    using Stage = typename FwdCfg<D, QT, NW>::Stage;
+    constexpr int BN = 64, STRIDE = Stage::STRIDE, KS = D / 16, CT = (D + 31) / 32;
+    auto kbuf = [&](int i) { return smem + i * Stage::BYTES; };
+    auto vbuf = [&](int i) { return smem + (4 + i) * Stage::BYTES; };
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) {
+        m_used[qt] = -INFINITY;
+        lsum[qt] = 0.f;
+        rsum[qt] = 0.f;
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) oacc[ct][qt] = f32x16_zero();
+    }
+    Stage kst, vst;
+    __syncthreads();
+    kst.load(kh, 0, tid);
+    vst.load(vh, 0, tid);
+    kst.store(kbuf(0), tid);
+    vst.store(vbuf(0), tid);
+    __syncthreads();
+    const int ntiles = (N + BN - 1) / BN;
+    for (int t = 0; t < ntiles; ++t) {
+        const char* kc = kbuf(t & 1);
+        const char* vc = vbuf(t & 1);
+        const bool more = t + 1 < ntiles;
+        if (more) {
+            kst.load(kh, (t + 1) * BN, tid);
+            vst.load(vh, (t + 1) * BN, tid);
+        }
+        if (wave_active) {
+#pragma unroll
+            for (int kt = 0; kt < BN / 32; ++kt) {
+                f32x16 s[QT];
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    const bf16x8 a = nat_frag(kc, STRIDE, 32 * kt + l32, ks, g);
+#pragma unroll
+                    for (int qt = 0; qt < QT; ++qt) s[qt] = mfma32(a, qf[qt][ks], ks == 0 ? f32x16_zero() : s[qt]);
+                }
+                const int key0 = t * BN + 32 * kt + 4 * g;
+                if (key0 + 28 >= N) {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i)
+                        if (key0 + 8 * (i / 4) + (i % 4) >= N) {
+#pragma unroll
+                            for (int qt = 0; qt < QT; ++qt) s[qt][i] = -INFINITY;
+                        }
+                }
+                bf16x8 pf[QT][2];
+#pragma unroll
+                for (int qt = 0; qt < QT; ++qt) {
+                    const float m2 = both_halves_max(max16(s[qt])) * cs;
+                    const float mn = fmaxf(m_used[qt], m2);  // finite: key 0 exists for every query
+                    const float alpha = fast_exp2(m_used[qt] - mn);
+                    m_used[qt] = mn;
+                    lsum[qt] *= alpha;
+                    rsum[qt] *= alpha;
+#pragma unroll
+                    for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) oacc[ct][qt][i] *= alpha;
+                    float rowsum = 0.f;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const float p = fast_exp2(fmaf(s[qt][i], cs, -mn));
+                        s[qt][i] = p;
+                        rowsum += p;
+                    }
+                    lsum[qt] += rowsum;
+                    pf[qt][0] = acc_to_frag(s[qt], 0);
+                    pf[qt][1] = acc_to_frag(s[qt], 1);
+                    rsum[qt] = frag_sum(pf[qt][1], frag_sum(pf[qt][0], rsum[qt]));
+                }
+#pragma unroll
+                for (int half = 0; half < 2; ++half)
+#pragma unroll
+                    for (int ct = 0; ct < CT; ++ct) {
+                        const bf16x8 a = tr_frag(vc, STRIDE, tr_off, ct, 2 * kt + half);
+#pragma unroll
+                        for (int qt = 0; qt < QT; ++qt) oacc[ct][qt] = mfma32(a, pf[qt][half], oacc[ct][qt]);
+                    }
+            }
+        }
+        if (more) {
+            kst.store(kbuf((t + 1) & 1), tid);
+            vst.store(vbuf((t + 1) & 1), tid);
+        }
+        __syncthreads();
+    }
+}
 
 template <int D, int QT, int NW>
 __global__ void __launch_bounds__(NW * 64)
@@ -45,10 +150,9 @@ avion_fwd_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const b
     constexpr int BN = Cfg::BN, BM = Cfg::BM, STRIDE = Stage::STRIDE;
     constexpr int KS = D / 16;         // 16-deep steps over the channels
     constexpr int CT = (D + 31) / 32;  // 32-channel tiles of O^T
-    constexpr int KT = BN / 32;        // 32-key sub-tiles of an LDS tile
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    auto kbuf = [&](int i) { return smem + i * Stage::BYTES; };
-    auto vbuf = [&](int i) { return smem + (3 + i) * Stage::BYTES; };
+    auto kbuf = [&](int ti) { return smem + (ti & 3) * Stage::BYTES; };
+    auto vbuf = [&](int ti) { return smem + (4 + (ti & 3)) * Stage::BYTES; };
 
     const int logical = xcd_local_id(blockIdx.x, nblocks);
     if (logical < 0) return;
@@ -79,130 +183,192 @@ avion_fwd_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const b
     float m_used[QT], lsum[QT], rsum[QT];
 #pragma unroll
     for (int qt = 0; qt < QT; ++qt) {
-        m_used[qt] = -INFINITY;
+        m_used[qt] = 0.f;
         lsum[qt] = 0.f;
         rsum[qt] = 0.f;
 #pragma unroll
         for (int ct = 0; ct < CT; ++ct) oacc[ct][qt] = f32x16_zero();
     }
 
+    // Tiles travel global -> registers -> LDS.  Two register sets alternate so that a tile has
+    // two full steps to arrive: tile t+3 is requested at the start of step t and written to LDS
+    // at the end of step t+1.
     const int ntiles = (N + BN - 1) / BN;
-    Stage kst, vst;
+    Stage kst[2], vst[2];
     if constexpr (D % 32 != 0) {
-        for (int i = 0; i < 3; ++i) Stage::zero_pad(vbuf(i), tid);
+        for (int i = 0; i < Cfg::NBUF; ++i) Stage::zero_pad(vbuf(i), tid);
     }
-    kst.load(kh, 0, tid);
-    vst.load(vh, 0, tid);
-    kst.store(kbuf(0), tid);
-    vst.store(vbuf(0), tid);
+    kst[0].load(kh, 0, tid);
+    vst[0].load(vh, 0, tid);
+    kst[0].store(kbuf(0), tid);
+    vst[0].store(vbuf(0), tid);
     if (ntiles > 1) {
-        kst.load(kh, BN, tid);
-        vst.load(vh, BN, tid);
-        kst.store(kbuf(1), tid);
-        vst.store(vbuf(1), tid);
+        kst[0].load(kh, BN, tid);
+        vst[0].load(vh, BN, tid);
+        kst[0].store(kbuf(1), tid);
+        vst[0].store(vbuf(1), tid);
     }
     __syncthreads();
 
-    // S^T of one LDS tile: [sub-tile of 32 keys][query tile], rows = keys, cols = queries
-    auto scores = [&](const char* kc, f32x16 (&s)[KT][QT]) {
+    // MFMAs of one unit in issue order: groups of QT sharing one LDS fragment; groups of the
+    // previous unit's P V update (kind 0, arg = half*CT+ct) alternate with groups of the next
+    // unit's S^T (kind 1, arg = ks).
+    constexpr int NA = 2 * CT, NB = KS, NG = NA + NB, NM = NG * QT;
+    struct Plan {
+        int kind[NG], arg[NG];
+    };
+    constexpr Plan plan = [] {
+        Plan p{};
+        int n = 0, ia = 0, ib = 0;
+        while (ia < NA || ib < NB) {
+            if (ia < NA) p.kind[n] = 0, p.arg[n++] = ia++;
+            if (ib < NB) p.kind[n] = 1, p.arg[n++] = ib++;
+        }
+        return p;
+    }();
+    constexpr int LA = 2;  // fragment reads run this many groups ahead
+    constexpr int NE = 16 * QT;    // score elements per lane and unit
+
+    // One unit: MASKED units replace scores of keys at or beyond N by -inf first.
+    auto unit = [&](auto masked, int key_base, const char* knext, int hnext, const char* vprev, int hprev,
+                    f32x16 (&s_c)[QT], f32x16 (&s_n)[QT], const u32x4 (&pf_p)[QT][2], u32x4 (&pf_c)[QT][2]) {
+        auto frag = [&](int gi) -> bf16x8 {
+            const int kd = plan.kind[gi], ar = plan.arg[gi];
+            if (kd == 0) return tr_frag(vprev, STRIDE, tr_off, ar % CT, 2 * hprev + ar / CT);
+            return nat_frag(knext, STRIDE, 32 * hnext + l32, ar, g);
+        };
+        if constexpr (decltype(masked)::value) {
+            const int key0 = key_base + 4 * g;
 #pragma unroll
-        for (int kt = 0; kt < KT; ++kt)
+            for (int i = 0; i < 16; ++i)
+                if (key0 + 8 * (i / 4) + (i % 4) >= N) {
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                const bf16x8 a = nat_frag(kc, STRIDE, 32 * kt + l32, ks, g);
+                    for (int qt = 0; qt < QT; ++qt) s_c[qt][i] = -INFINITY;
+                }
+        }
+        bf16x8 fr[NG];
 #pragma unroll
-                for (int qt = 0; qt < QT; ++qt)
-                    s[kt][qt] = mfma32(a, qf[qt][ks], ks == 0 ? f32x16_zero() : s[kt][qt]);
+        for (int gi = 0; gi < LA; ++gi) fr[gi] = frag(gi);
+        const bf16x2 ones = {(bf16)1.0f, (bf16)1.0f};
+#pragma unroll
+        for (int gi = 0; gi < NG; ++gi) {
+            if (gi + LA < NG) fr[gi + LA] = frag(gi + LA);
+            const int kd = plan.kind[gi], ar = plan.arg[gi];
+#pragma unroll
+            for (int qt = 0; qt < QT; ++qt) {
+                if (kd == 0)
+                    oacc[ar % CT][qt] = mfma32(fr[gi], as_bf16x8(pf_p[qt][ar / CT]), oacc[ar % CT][qt]);
+                else
+                    s_n[qt] = mfma32(fr[gi], qf[qt][ar], ar == 0 ? f32x16_zero() : s_n[qt]);
+                // vector-ALU share of this MFMA slot
+                const int m = gi * QT + qt;
+                const int e0 = m * NE / NM, e1 = (m + 1) * NE / NM;
+#pragma unroll
+                for (int e = e0; e < e1; ++e) {
+                    const int eq = e / 16, i = e % 16;
+                    const float p = fast_exp2(fmaf(s_c[eq][i], cs, -m_used[eq]));
+                    s_c[eq][i] = p;
+                    lsum[eq] += p;
+                    if (i % 2 == 1) {
+                        // the second row sum runs over the weights as rounded to bf16, i.e. the
+                        // numbers the second contraction multiplies V with; O is divided by it
+                        const unsigned w = pack_bf16(s_c[eq][i - 1], p);
+                        pf_c[eq][i / 8][(i / 2) % 4] = w;
+                        rsum[eq] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), ones, rsum[eq], false);
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    };
+    // P V update of one unit outside the pipeline (the very last one)
+    auto pv_only = [&](const char* vb, int hq, const u32x4 (&pf)[QT][2]) {
+#pragma unroll
+        for (int half = 0; half < 2; ++half)
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct) {
+                const bf16x8 a = tr_frag(vb, STRIDE, tr_off, ct, 2 * hq + half);
+#pragma unroll
+                for (int qt = 0; qt < QT; ++qt) oacc[ct][qt] = mfma32(a, as_bf16x8(pf[qt][half]), oacc[ct][qt]);
             }
     };
 
-    // one pipeline step on tile t: `cur` holds S^T of tile t, `nxt` receives S^T of tile t+1
-    auto step = [&](int t, f32x16 (&cur)[KT][QT], f32x16 (&nxt)[KT][QT]) {
-        const bool have1 = t + 1 < ntiles, have2 = t + 2 < ntiles;
-        if (have2) {
-            kst.load(kh, (t + 2) * BN, tid);
-            vst.load(vh, (t + 2) * BN, tid);
+    f32x16 sA[QT], sB[QT];
+    u32x4 pfA[QT][2], pfB[QT][2];
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt)
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const u32x4 z = {0u, 0u, 0u, 0u};
+            pfA[qt][i] = z, pfB[qt][i] = z;
+        }
+    if (wave_active) {
+        // S^T of unit 0 and the per-query reference maximum over its (valid) keys
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const bf16x8 a = nat_frag(kbuf(0), STRIDE, l32, ks, g);
+#pragma unroll
+            for (int qt = 0; qt < QT; ++qt) sA[qt] = mfma32(a, qf[qt][ks], ks == 0 ? f32x16_zero() : sA[qt]);
+        }
+#pragma unroll
+        for (int qt = 0; qt < QT; ++qt) {
+            f32x16 tmp = sA[qt];
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+                if (4 * g + 8 * (i / 4) + (i % 4) >= N) tmp[i] = -INFINITY;
+            m_used[qt] = both_halves_max(max16(tmp)) * cs;
+        }
+    }
+    wait_all_loads();
+    if (ntiles > 2) {
+        kst[0].load(kh, 2 * BN, tid);
+        vst[0].load(vh, 2 * BN, tid);
+    }
+
+    // one step = one 64-key tile = two units; `in` receives tile t+3, `out` holds tile t+2
+    auto step = [&](int t, Stage& k_in, Stage& v_in, const Stage& k_out, const Stage& v_out) {
+        if (t + 3 < ntiles) {
+            k_in.load(kh, (t + 3) * BN, tid);
+            v_in.load(vh, (t + 3) * BN, tid);
         }
         if (wave_active) {
-            if (have1) scores(kbuf((t + 1) % 3), nxt);
-            const char* vc = vbuf(t % 3);
-            if ((t + 1) * BN > N) {  // ragged last tile: keys at or beyond N get weight 0
-#pragma unroll
-                for (int kt = 0; kt < KT; ++kt) {
-                    const int key0 = t * BN + 32 * kt + 4 * g;
-#pragma unroll
-                    for (int i = 0; i < 16; ++i)
-                        if (key0 + 8 * (i / 4) + (i % 4) >= N) {
-#pragma unroll
-                            for (int qt = 0; qt < QT; ++qt) cur[kt][qt][i] = -INFINITY;
-                        }
-                }
+            const char* vprev = vbuf(t - 1 < 0 ? 0 : t - 1);
+            __builtin_amdgcn_sched_barrier(0);
+            // unit 2t: current = A; next = unit 2t+1 (K tile t, second half); previous = unit 2t-1
+            // (V tile t-1, second half; at t = 0 its weights are zero and V tile 0 stands in)
+            // unit 2t+1: current = B; next = unit 2t+2 (K tile t+1, first half; past the last tile a
+            // stale buffer whose scores are never used); previous = unit 2t (V tile t, first half)
+            if ((t + 1) * BN > N) {
+                unit(std::true_type{}, t * BN, kbuf(t), 1, vprev, 1, sA, sB, pfB, pfA);
+                unit(std::true_type{}, t * BN + 32, kbuf(t + 1), 0, vbuf(t), 0, sB, sA, pfA, pfB);
+            } else {
+                unit(std::false_type{}, 0, kbuf(t), 1, vprev, 1, sA, sB, pfB, pfA);
+                unit(std::false_type{}, 0, kbuf(t + 1), 0, vbuf(t), 0, sB, sA, pfA, pfB);
             }
-            // online softmax in base 2: weights are exp2(cs*s - m_used)
-            bf16x8 pf[KT][QT][2];
-#pragma unroll
-            for (int qt = 0; qt < QT; ++qt) {
-                float mx = max16(cur[0][qt]);
-#pragma unroll
-                for (int kt = 1; kt < KT; ++kt) mx = max3(mx, max16(cur[kt][qt]), mx);
-                const float m2 = both_halves_max(mx) * cs;
-                if (__builtin_amdgcn_ballot_w64(m2 > m_used[qt] + kLazyBinades) != 0ull) {
-                    const float mn = fmaxf(m_used[qt], m2);
-                    const float alpha = fast_exp2(m_used[qt] - mn);
-                    m_used[qt] = mn;
-                    lsum[qt] *= alpha;
-                    rsum[qt] *= alpha;
-#pragma unroll
-                    for (int ct = 0; ct < CT; ++ct)
-#pragma unroll
-                        for (int i = 0; i < 16; ++i) oacc[ct][qt][i] *= alpha;
-                }
-                const float nm = -m_used[qt];
-#pragma unroll
-                for (int kt = 0; kt < KT; ++kt) {
-                    float rowsum = 0.f;
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const float p = fast_exp2(fmaf(cur[kt][qt][i], cs, nm));
-                        cur[kt][qt][i] = p;
-                        rowsum += p;
-                    }
-                    lsum[qt] += rowsum;
-                    pf[kt][qt][0] = acc_to_frag(cur[kt][qt], 0);
-                    pf[kt][qt][1] = acc_to_frag(cur[kt][qt], 1);
-                    // Second row sum, over the weights as rounded to bf16, i.e. exactly the numbers
-                    // the second contraction multiplies V with.  O is divided by this one, which
-                    // makes it a true convex combination of value rows (the rounding of a dominant
-                    // weight cancels); LSE uses the unrounded sum.
-                    rsum[qt] = frag_sum(pf[kt][qt][1], frag_sum(pf[kt][qt][0], rsum[qt]));
-                }
-            }
-            // O^T += V^T P^T
-#pragma unroll
-            for (int kt = 0; kt < KT; ++kt)
-#pragma unroll
-                for (int half = 0; half < 2; ++half)
-#pragma unroll
-                    for (int ct = 0; ct < CT; ++ct) {
-                        const bf16x8 a = tr_frag(vc, STRIDE, tr_off, ct, 2 * kt + half);
-#pragma unroll
-                        for (int qt = 0; qt < QT; ++qt) oacc[ct][qt] = mfma32(a, pf[kt][qt][half], oacc[ct][qt]);
-                    }
         }
-        if (have2) {
-            kst.store(kbuf((t + 2) % 3), tid);
-            vst.store(vbuf((t + 2) % 3), tid);
+        if (t + 2 < ntiles) {
+            k_out.store(kbuf(t + 2), tid);
+            v_out.store(vbuf(t + 2), tid);
         }
         __syncthreads();
     };
-
-    f32x16 sa[KT][QT], sb[KT][QT];
-    if (wave_active) scores(kbuf(0), sa);
-    wait_all_loads();
     for (int t = 0; t < ntiles; t += 2) {
-        step(t, sa, sb);
-        if (t + 1 < ntiles) step(t + 1, sb, sa);
+        step(t, kst[1], vst[1], kst[0], vst[0]);
+        if (t + 1 < ntiles) step(t + 1, kst[0], vst[0], kst[1], vst[1]);
     }
+    if (wave_active) pv_only(vbuf(ntiles - 1), 1, pfB);
+
+    // overflow of the fixed reference: redo this workgroup's rows with the running maximum
+    bool bad = false;
+    if (wave_active) {
+#pragma unroll
+        for (int qt = 0; qt < QT; ++qt) {
+            const float l = both_halves_sum(lsum[qt]);
+            bad = bad || !(l <= kRowSumLimit);
+        }
+    }
+    if (__syncthreads_or(bad ? 1 : 0))
+        avion_fwd_safe_pass<D, QT, NW>(smem, kh, vh, qf, oacc, m_used, lsum, rsum, N, cs, wave_active, tid, l32, g, tr_off);
 
     if (!wave_active) return;
 #pragma unroll

@@ -116,6 +116,26 @@ def test_large_magnitude_scores():
     assert np.abs(out["lse"].double().cpu().numpy() - rl).max() <= 2e-3 * np.abs(rl).max()
 
 
+def test_scores_far_above_the_first_keys_take_the_running_max_path():
+    # The forward kernel references every query's weights to the maximum over its first 32 keys and
+    # falls back to a running maximum when a later score is ~100 binades larger.  Here the keys
+    # from 64 on are 16 times larger and scale = 1: later scores exceed the early ones by hundreds
+    # of binades, so this exercises the fallback; O and LSE must still match the oracle.
+    import oracle
+    for d in (64, 80):
+        w = si.small_workload(1, 2, 200, d, seed=1234 + d, scale=1.0)
+        x = si.make_inputs(w)
+        big = si.bf16_bits_to_f32(x["k"][:, 64:]) * np.float32(16.0)
+        x["k"][:, 64:] = si.f32_to_bf16_bits(big)          # exact: power of two
+        out = gh.run_hip(w, x)
+        ro, rl = oracle.fwd(x["q"], x["k"], x["v"], w.scale)
+        o = gh.bf16_tensor_to_f64(out["o"])
+        lse = out["lse"].double().cpu().numpy()
+        assert np.all(np.isfinite(o)) and np.all(np.isfinite(lse))
+        assert np.abs(o - ro).max() <= 2.0 ** -7 * np.abs(ro).max()      # one bf16 ulp of near one-hot rows
+        assert np.abs(lse - rl).max() <= 2e-6 * np.abs(rl).max() + 1e-3  # fp32 LSE of magnitude ~1e3
+
+
 def test_bad_arguments_raise_on_gpu_tensors():
     import torch
     import paper_2309_16669_amd as av
