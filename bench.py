@@ -27,7 +27,12 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published figure
 
 # HBM bytes per launch (FETCH_SIZE + WRITE_SIZE from rocprofv3 --pmc, scaled by a copy kernel of
 # known size); filled in from the summaries under profiles/ -- None until measured.
-MEASURED_HBM_BYTES_PER_LAUNCH = {}
+MEASURED_HBM_BYTES_PER_LAUNCH = {
+    # profiles/hbm_traffic_vitb_batch.txt: FETCH_SIZE x 2.0 (copy-kernel factor) + WRITE_SIZE x 1.0
+    ("vitb_batch", "avion_fwd_kernel"): 311.2e6,
+    ("vitb_batch", "avion_dq_kernel"): 478.1e6,
+    ("vitb_batch", "avion_dkdv_kernel"): 478.1e6,
+}
 
 
 def log(*a):
@@ -77,6 +82,9 @@ def main():
     ap.add_argument("--workload", default="vitb_batch")
     ap.add_argument("--cpu-clips", type=int, default=32)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain device copy of Q (known size) so that HBM counters of a "
+                         "rocprofv3 --pmc run can be scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (attention shards over batch and heads with no "
@@ -108,6 +116,13 @@ def main():
     dq, dk, dv = (torch.empty_like(q) for _ in range(3))
     ws = torch.empty(av.attn_bwd_workspace_bytes(w.B, w.H, w.N, w.d), dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream()
+
+    if args.calibration_copy:
+        scratch = torch.empty_like(q)
+        for _ in range(3):
+            scratch.copy_(q)          # reads and writes q.numel()*2 bytes each
+        torch.cuda.synchronize()
+        log(f"[bench] calibration copy: {q.numel() * 2} bytes read, {q.numel() * 2} bytes written per launch")
 
     def fwd():
         av.attn_fwd(q, k, v, o, lse, w.scale, stream)
