@@ -126,7 +126,7 @@ int dq_dispatch(const bf16* q, const bf16* k, const bf16* v, const bf16* o, cons
 {
     if constexpr (D == 64) {
         static const int vq = variant("DQ", 0);
-        if (vq == 0) return launch_dq<D, 2, 4>(q, k, v, o, dO, lse, dq, delta, B, H, N, scale, st);
+        if (vq == 2) return launch_dq<D, 2, 4>(q, k, v, o, dO, lse, dq, delta, B, H, N, scale, st);
     }
     return launch_dq<D, 1, 4>(q, k, v, o, dO, lse, dq, delta, B, H, N, scale, st);
 }

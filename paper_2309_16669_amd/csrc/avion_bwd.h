@@ -80,10 +80,24 @@ avion_dq_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf
     }
 
     f32x16 acc[CT][QT];
+    // With one query tile per wavefront there are registers to spare for a block holding -delta of
+    // the lane's query in every element: used as the initial value of the dP accumulator, it makes
+    // the MFMAs deliver dP - delta and saves one vector-ALU instruction per score.
+    constexpr bool SEED_DELTA = QT == 1;
+    f32x16 ndl[SEED_DELTA ? QT : 1];
 #pragma unroll
-    for (int qt = 0; qt < QT; ++qt)
+    for (int qt = 0; qt < QT; ++qt) {
 #pragma unroll
         for (int ct = 0; ct < CT; ++ct) acc[ct][qt] = f32x16_zero();
+        if constexpr (SEED_DELTA) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) ndl[qt][i] = -dl[qt];
+        }
+    }
+    auto dp_seed = [&](int qt) -> f32x16 {
+        if constexpr (SEED_DELTA) return ndl[qt];
+        return f32x16_zero();
+    };
 
     Stage kst, vst;
     if constexpr (D % 32 != 0) {
@@ -118,7 +132,7 @@ avion_dq_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf
 #pragma unroll
                     for (int qt = 0; qt < QT; ++qt) {
                         s[qt] = mfma32(ak, qf[qt][ks], ks == 0 ? f32x16_zero() : s[qt]);
-                        dp[qt] = mfma32(av, gf[qt][ks], ks == 0 ? f32x16_zero() : dp[qt]);
+                        dp[qt] = mfma32(av, gf[qt][ks], ks == 0 ? dp_seed(qt) : dp[qt]);
                     }
                 }
                 bf16x8 df[QT][2];
@@ -128,7 +142,7 @@ avion_dq_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf
 #pragma unroll
                     for (int i = 0; i < 16; ++i) {
                         const float p = fast_exp2(fmaf(s[qt][i], cs, nl));
-                        s[qt][i] = p * (dp[qt][i] - dl[qt]);
+                        s[qt][i] = SEED_DELTA ? p * dp[qt][i] : p * (dp[qt][i] - dl[qt]);
                     }
                     // keys beyond N were staged as zero rows; force their dS to zero as well so
                     // that an overflowing weight cannot turn 0 * inf into NaN
@@ -159,22 +173,16 @@ avion_dq_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf
         __syncthreads();
     }
 
+    // the loop ended with a barrier: the tile buffers are free and stage the output rows
     if (!wave_active) return;
+    char* region = smem + wave * RowStore<D>::BYTES;
 #pragma unroll
     for (int qt = 0; qt < QT; ++qt) {
-        const int row = q0 + 32 * qt + l32;
-        if (row < N) {
-            bf16* drow = dq + head_off + (long)row * rs;
+        const int row0 = q0 + 32 * qt;
+        f32x16 tile[CT];
 #pragma unroll
-            for (int ct = 0; ct < CT; ++ct)
-#pragma unroll
-                for (int a4 = 0; a4 < 4; ++a4) {
-                    const int c0 = 32 * ct + 8 * a4 + 4 * g;
-                    if (c0 < D)
-                        store_bf16x4(drow + c0, acc[ct][qt][4 * a4 + 0] * scale, acc[ct][qt][4 * a4 + 1] * scale,
-                                     acc[ct][qt][4 * a4 + 2] * scale, acc[ct][qt][4 * a4 + 3] * scale);
-                }
-        }
+        for (int ct = 0; ct < CT; ++ct) tile[ct] = acc[ct][qt];
+        RowStore<D>::run(region, tile, scale, dq + head_off + (long)row0 * rs, rs, N - row0, lane);
     }
 }
 
@@ -186,7 +194,8 @@ avion_dq_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf
 // queued behind another one blocks everything after it:
 //   matrix cores : S and dP of the NEXT unit (into a second accumulator pair), and the dV^T, dK^T
 //                  updates of the PREVIOUS unit (from its saved bf16 P and dS fragments);
-//   vector ALUs  : P = exp2(cs*S - lc), dS = P o (dP - delta) of the CURRENT unit, rounded to bf16.
+//   vector ALUs  : P = exp2(cs*S - lc), dS = P o (dP - delta) of the CURRENT unit, rounded to bf16
+//                  (the dP accumulator starts from -delta, so the subtraction costs nothing).
 template <int D, int NW>
 struct DkvCfg {
     static constexpr int BQ = 64;  // queries per LDS tile (two units)
@@ -212,7 +221,7 @@ avion_dkdv_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const 
     constexpr int KS = D / 16;
     constexpr int CT = (D + 31) / 32;
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    // per buffer: Q tile | dO tile | lc[BQ] | dl[BQ]
+    // per buffer: Q tile | dO tile | lc[BQ] | -delta[BQ]
     constexpr int OFF_G = Stage::BYTES, OFF_ROW = 2 * Stage::BYTES;
     auto tilebuf = [&](int ti) { return smem + (ti & 3) * Cfg::BUF_BYTES; };
 
@@ -259,7 +268,7 @@ avion_dkdv_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const 
             const int tok = r0 + tid;
             // queries beyond N get weight exp2(-inf) = 0, hence dS = 0 as well
             lc_r = tok < N ? lrow[tok] * kLog2e : INFINITY;
-            dl_r = tok < N ? drow[tok] : 0.f;
+            dl_r = tok < N ? -drow[tok] : 0.f;  // stored negated: it seeds the dP accumulator
         }
     };
     auto store_tile = [&](char* buf) {
@@ -286,13 +295,28 @@ avion_dkdv_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const 
     __syncthreads();
 
     // S and dP of one unit: rows = 32 queries (half hq of the tile), cols = this wave's 32 keys
+    // -delta of the 16 queries this lane's accumulator registers belong to (broadcast LDS reads);
+    // used as the initial value of the dP accumulator, so that the MFMAs deliver dP - delta
+    auto neg_delta_rows = [&](const char* buf, int hq) -> f32x16 {
+        const float* rowv = reinterpret_cast<const float*>(buf + OFF_ROW) + BQ + 32 * hq + 4 * g;
+        f32x16 r;
+#pragma unroll
+        for (int a4 = 0; a4 < 4; ++a4) {
+            const f32x4 d4 = *reinterpret_cast<const f32x4*>(rowv + 8 * a4);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) r[4 * a4 + e] = d4[e];
+        }
+        return r;
+    };
+    // S and dP - delta of one unit: rows = 32 queries (half hq of the tile), cols = this wave's keys
     auto scores = [&](const char* buf, int hq, f32x16& s, f32x16& dp) {
+        dp = neg_delta_rows(buf, hq);
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             const bf16x8 aq = nat_frag(buf, STRIDE, 32 * hq + l32, ks, g);
             const bf16x8 ag = nat_frag(buf + OFF_G, STRIDE, 32 * hq + l32, ks, g);
             s = mfma32(aq, kf[ks], ks == 0 ? f32x16_zero() : s);
-            dp = mfma32(ag, vf[ks], ks == 0 ? f32x16_zero() : dp);
+            dp = mfma32(ag, vf[ks], dp);
         }
     };
     // dV^T += dO^T P ,  dK^T += Q^T dS  of one unit (contraction over its 32 queries, 2 steps)
@@ -345,11 +369,11 @@ avion_dkdv_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const 
         };
         const float* rowv = reinterpret_cast<const float*>(bcur + OFF_ROW) + 32 * hcur + 4 * g;
         bf16x8 fr[NM];
-        f32x4 l4[4], d4[4];
+        f32x4 l4[4];
 #pragma unroll
         for (int i = 0; i < LA; ++i) fr[i] = frag(i);
         l4[0] = *reinterpret_cast<const f32x4*>(rowv);
-        d4[0] = *reinterpret_cast<const f32x4*>(rowv + BQ);
+        dp_n = neg_delta_rows(bnext, hnext);
 #pragma unroll
         for (int i = 0; i < NM; ++i) {
             if (i + LA < NM) fr[i + LA] = frag(i + LA);
@@ -357,18 +381,16 @@ avion_dkdv_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const 
             if (kd == 0) dva[ar % CT] = mfma32(fr[i], as_bf16x8(pf_p[ar / CT]), dva[ar % CT]);
             if (kd == 1) dka[ar % CT] = mfma32(fr[i], as_bf16x8(df_p[ar / CT]), dka[ar % CT]);
             if (kd == 2) s_n = mfma32(fr[i], kf[ar], ar == 0 ? f32x16_zero() : s_n);
-            if (kd == 3) dp_n = mfma32(fr[i], vf[ar], ar == 0 ? f32x16_zero() : dp_n);
+            if (kd == 3) dp_n = mfma32(fr[i], vf[ar], dp_n);
             // vector-ALU share of this slot: elements e0..e1-1 of the current unit
             const int e0 = i * 16 / NM, e1 = (i + 1) * 16 / NM;
 #pragma unroll
             for (int e = e0; e < e1; ++e) {
-                if (e % 4 == 0 && e + 4 < 16) {  // row values of the next four queries
+                if (e % 4 == 0 && e + 4 < 16)  // LSE*log2e of the next four queries
                     l4[e / 4 + 1] = *reinterpret_cast<const f32x4*>(rowv + 8 * (e / 4 + 1));
-                    d4[e / 4 + 1] = *reinterpret_cast<const f32x4*>(rowv + BQ + 8 * (e / 4 + 1));
-                }
                 const float pe = fast_exp2(fmaf(s_c[e], cs, -l4[e / 4][e % 4]));
                 s_c[e] = pe;
-                dp_c[e] = pe * (dp_c[e] - d4[e / 4][e % 4]);
+                dp_c[e] = pe * dp_c[e];  // dp_c already holds dP - delta
                 if (e % 2 == 1) {
                     pf_c[e / 8][(e / 2) % 4] = pack_bf16(s_c[e - 1], s_c[e]);
                     df_c[e / 8][(e / 2) % 4] = pack_bf16(dp_c[e - 1], dp_c[e]);
@@ -406,25 +428,10 @@ avion_dkdv_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const 
         __syncthreads();
     }
 
+    if (wave_active) accumulate(tilebuf(ntiles - 1), 1, pfB, dfB);  // the last unit's contribution
+    __syncthreads();  // all tile reads are done: the buffers now stage the output rows
     if (!wave_active) return;
-    accumulate(tilebuf(ntiles - 1), 1, pfB, dfB);  // the last unit's contribution
-    {
-        const int row = k0 + l32;
-        if (row < N) {
-            bf16* dkrow = dk + head_off + (long)row * rs;
-            bf16* dvrow = dv + head_off + (long)row * rs;
-#pragma unroll
-            for (int ct = 0; ct < CT; ++ct)
-#pragma unroll
-                for (int a4 = 0; a4 < 4; ++a4) {
-                    const int c0 = 32 * ct + 8 * a4 + 4 * g;
-                    if (c0 < D) {
-                        store_bf16x4(dkrow + c0, dka[ct][4 * a4 + 0] * scale, dka[ct][4 * a4 + 1] * scale,
-                                     dka[ct][4 * a4 + 2] * scale, dka[ct][4 * a4 + 3] * scale);
-                        store_bf16x4(dvrow + c0, dva[ct][4 * a4 + 0], dva[ct][4 * a4 + 1], dva[ct][4 * a4 + 2],
-                                     dva[ct][4 * a4 + 3]);
-                    }
-                }
-        }
-    }
+    char* region = smem + wave * RowStore<D>::BYTES;
+    RowStore<D>::run(region, dka, scale, dk + head_off + (long)k0 * rs, rs, N - k0, lane);
+    RowStore<D>::run(region, dva, 1.0f, dv + head_off + (long)k0 * rs, rs, N - k0, lane);
 }

@@ -250,11 +250,49 @@ DEVINL int xcd_local_id(int block, int nblocks)
     return logical < nblocks ? logical : -1;
 }
 
-// store 4 consecutive channels (fp32 -> bf16) of one token
-DEVINL void store_bf16x4(bf16* dst, float a, float b, float c, float d)
-{
-    u32x2 w;
-    w[0] = pack_bf16(a, b);
-    w[1] = pack_bf16(c, d);
-    *reinterpret_cast<u32x2*>(dst) = w;
-}
+// Epilogue store of one wavefront's 32 x D result tile held as transposed accumulators
+// (lane = token row l32 of the tile, register v of channel tile ct = channel
+// 32*ct + 8*(v/4) + 4*g + v%4).  Written straight from that layout every lane would store 8-byte
+// pieces of 32 different rows; instead the tile is rounded to bf16, laid out row-major in a
+// per-wavefront LDS region and read back so that 8 (D=64) or 10 (D=80) consecutive lanes store one
+// full row with 16-byte pieces.  `region` must not be in use by any other wavefront; LDS
+// operations of one wavefront execute in order, so no barrier is needed in between.
+template <int D>
+struct RowStore {
+    static constexpr int CT = (D + 31) / 32;
+    static constexpr int STRIDE = D * 2 + 16;
+    static constexpr int BYTES = 32 * STRIDE;  // per wavefront
+    static constexpr int CH = D / 8;           // 16-byte chunks per row
+
+    DEVINL static void run(char* region, const f32x16 (&acc)[CT], float mul, bf16* dst, long rs, int rows_valid, int lane)
+    {
+        const int l32 = lane % 32, g = lane / 32;
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+            for (int a4 = 0; a4 < 4; ++a4) {
+                const int c0 = 32 * ct + 8 * a4 + 4 * g;
+                if (c0 < D) {
+                    u32x2 w;
+                    w[0] = pack_bf16(acc[ct][4 * a4 + 0] * mul, acc[ct][4 * a4 + 1] * mul);
+                    w[1] = pack_bf16(acc[ct][4 * a4 + 2] * mul, acc[ct][4 * a4 + 3] * mul);
+                    *reinterpret_cast<u32x2*>(region + l32 * STRIDE + c0 * 2) = w;
+                }
+            }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        constexpr int TOTAL = 32 * CH;
+#pragma unroll
+        for (int i = 0; i < (TOTAL + 63) / 64; ++i) {
+            const int idx = lane + 64 * i;
+            const int row = idx / CH, ch = idx % CH;
+            if (idx < TOTAL && row < rows_valid) {
+                const u32x4 val = *reinterpret_cast<const u32x4*>(region + row * STRIDE + ch * 16);
+                *reinterpret_cast<u32x4*>(dst + (long)row * rs + ch * 8) = val;
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    }
+};

@@ -370,24 +370,24 @@ avion_fwd_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const b
     if (__syncthreads_or(bad ? 1 : 0))
         avion_fwd_safe_pass<D, QT, NW>(smem, kh, vh, qf, oacc, m_used, lsum, rsum, N, cs, wave_active, tid, l32, g, tr_off);
 
+    // every wavefront is past its last tile read (barrier above): the tile buffers are free and
+    // serve as the per-wavefront staging area of the output rows
     if (!wave_active) return;
+    char* region = smem + wave * RowStore<D>::BYTES;
 #pragma unroll
     for (int qt = 0; qt < QT; ++qt) {
         const float l = both_halves_sum(lsum[qt]);
         const float inv = 1.0f / both_halves_sum(rsum[qt]);
-        const int row = q0 + 32 * qt + l32;
-        if (row < N) {
-            bf16* orow = oh + (long)row * rs;
+        const int row0 = q0 + 32 * qt;
+        f32x16 tile[CT];
 #pragma unroll
-            for (int ct = 0; ct < CT; ++ct)
+        for (int ct = 0; ct < CT; ++ct) tile[ct] = oacc[ct][qt];
+        // each lane scales by its own query's divisor before the rows are transposed
 #pragma unroll
-                for (int a4 = 0; a4 < 4; ++a4) {
-                    const int c0 = 32 * ct + 8 * a4 + 4 * g;
-                    if (c0 < D)
-                        store_bf16x4(orow + c0, oacc[ct][qt][4 * a4 + 0] * inv, oacc[ct][qt][4 * a4 + 1] * inv,
-                                     oacc[ct][qt][4 * a4 + 2] * inv, oacc[ct][qt][4 * a4 + 3] * inv);
-                }
-            if (g == 0) lse[(long)bh * N + row] = (m_used[qt] + __builtin_amdgcn_logf(l)) * kLn2;
-        }
+        for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) tile[ct][i] *= inv;
+        RowStore<D>::run(region, tile, 1.0f, oh + (long)row0 * rs, rs, N - row0, lane);
+        if (g == 0 && row0 + l32 < N) lse[(long)bh * N + row0 + l32] = (m_used[qt] + __builtin_amdgcn_logf(l)) * kLn2;
     }
 }
