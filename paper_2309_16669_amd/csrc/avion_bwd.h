@@ -261,22 +261,28 @@ avion_dkdv_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const 
 
     Stage qst, gst;
     float lc_r = 0.f, dl_r = 0.f;
+    constexpr int RPW = BQ / NW;  // per-query scalars staged by each wavefront
+    const int row_slot = wave * RPW + lane;
+    // The per-query scalars are fetched raw (row index clamped, no dependent arithmetic) so that
+    // nothing waits for them until the tile is written to LDS, one iteration later.
     auto load_tile = [&](int r0) {
         qst.load(qh, r0, tid);
         gst.load(gh, r0, tid);
-        if (tid < BQ) {
-            const int tok = r0 + tid;
-            // queries beyond N get weight exp2(-inf) = 0, hence dS = 0 as well
-            lc_r = tok < N ? lrow[tok] * kLog2e : INFINITY;
-            dl_r = tok < N ? -drow[tok] : 0.f;  // stored negated: it seeds the dP accumulator
+        if (lane < RPW) {  // every wavefront fetches an equal share of the per-query scalars
+            const int tok = min(r0 + row_slot, N - 1);
+            lc_r = lrow[tok];
+            dl_r = drow[tok];
         }
     };
-    auto store_tile = [&](char* buf) {
+    auto store_tile = [&](char* buf, int r0) {
         qst.store(buf, tid);
         gst.store(buf + OFF_G, tid);
-        if (tid < BQ) {
-            reinterpret_cast<float*>(buf + OFF_ROW)[tid] = lc_r;
-            reinterpret_cast<float*>(buf + OFF_ROW)[BQ + tid] = dl_r;
+        if (lane < RPW) {
+            const bool valid = r0 + row_slot < N;
+            // queries beyond N get weight exp2(-inf) = 0, hence dS = 0 as well; delta is stored
+            // negated because it seeds the dP accumulator
+            reinterpret_cast<float*>(buf + OFF_ROW)[row_slot] = valid ? lc_r * kLog2e : INFINITY;
+            reinterpret_cast<float*>(buf + OFF_ROW)[BQ + row_slot] = valid ? -dl_r : 0.f;
         }
     };
     if constexpr (D % 32 != 0) {
@@ -287,11 +293,12 @@ avion_dkdv_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const 
     }
     const int ntiles = (N + BQ - 1) / BQ;
     load_tile(0);
-    store_tile(tilebuf(0));
+    store_tile(tilebuf(0), 0);
     if (ntiles > 1) {
         load_tile(BQ);
-        store_tile(tilebuf(1));
+        store_tile(tilebuf(1), BQ);
     }
+    if (ntiles > 2) load_tile(2 * BQ);
     __syncthreads();
 
     // S and dP of one unit: rows = 32 queries (half hq of the tile), cols = this wave's 32 keys
@@ -410,21 +417,23 @@ avion_dkdv_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const 
     if (wave_active) scores(tilebuf(0), 0, sA, dpA);
     wait_all_loads();
 
+    // Tile t+2 travels through registers: fetched during iteration t-1, written to LDS between the
+    // two units of iteration t (its buffer held tile t-2, which nobody reads after the barrier that
+    // ended iteration t-1), first read after the barrier that ends iteration t.  Neither the global
+    // loads nor the LDS writes are waited for at the barrier itself.
     for (int t = 0; t < ntiles; ++t) {
-        if (t + 2 < ntiles) load_tile((t + 2) * BQ);
-        if (wave_active) {
-            const char* bprev = tilebuf(t - 1 < 0 ? 0 : t - 1);
-            const char* bcur = tilebuf(t);
-            const char* bnext = tilebuf(t + 1);
-            __builtin_amdgcn_sched_barrier(0);
-            // unit 2t: current = A; next = unit 2t+1 (same tile, second half); previous = unit 2t-1
-            // (second half of tile t-1; at t = 0 its fragments are zero)
-            unit(bcur, 1, bcur, 0, bprev, 1, sA, dpA, sB, dpB, pfB, dfB, pfA, dfA);
-            // unit 2t+1: current = B; next = unit 2t+2 (first half of tile t+1; past the last tile
-            // this reads a stale buffer whose result is never used); previous = unit 2t
-            unit(bnext, 0, bcur, 1, bcur, 0, sB, dpB, sA, dpA, pfA, dfA, pfB, dfB);
-        }
-        if (t + 2 < ntiles) store_tile(tilebuf(t + 2));
+        const char* bprev = tilebuf(t - 1 < 0 ? 0 : t - 1);
+        const char* bcur = tilebuf(t);
+        const char* bnext = tilebuf(t + 1);
+        // unit 2t: current = A; next = unit 2t+1 (same tile, second half); previous = unit 2t-1
+        // (second half of tile t-1; at t = 0 its fragments are zero)
+        if (wave_active) unit(bcur, 1, bcur, 0, bprev, 1, sA, dpA, sB, dpB, pfB, dfB, pfA, dfA);
+        if (t + 2 < ntiles) store_tile(tilebuf(t + 2), (t + 2) * BQ);
+        if (t + 3 < ntiles) load_tile((t + 3) * BQ);
+        __builtin_amdgcn_sched_barrier(0);
+        // unit 2t+1: current = B; next = unit 2t+2 (first half of tile t+1; past the last tile
+        // this reads a stale buffer whose result is never used); previous = unit 2t
+        if (wave_active) unit(bnext, 0, bcur, 1, bcur, 0, sB, dpB, sA, dpA, pfA, dfA, pfB, dfB);
         __syncthreads();
     }
 
