@@ -67,8 +67,9 @@ int avion_attn_fwd(const void *q, const void *k, const void *v, void *o, float *
                    int B, int H, int N, int d, float scale, void *stream);
 
 /*
- * Bytes of device workspace avion_attn_bwd needs for this shape: B*H*N fp32 (the row sums of
- * dO o O) rounded up to 256 bytes -- linear in N, never N^2.  Returns 0 for an unsupported shape.
+ * Bytes of device workspace avion_attn_bwd needs for this shape: two fp32 per (batch, head, query)
+ * (the row sums of dO o O and a rescaled copy of lse), with N rounded up to a multiple of 64 and
+ * the total to 256 bytes -- linear in N, never N^2.  Returns 0 for an unsupported shape.
  */
 size_t avion_attn_bwd_workspace_bytes(int B, int H, int N, int d);
 
@@ -93,12 +94,13 @@ int avion_attn_bwd(const void *q, const void *k, const void *v, const void *o, c
  * avion_attn_bwd(...) is exactly avion_attn_bwd_dq(...) followed by avion_attn_bwd_dkdv(...) on
  * the same stream with the same workspace.
  *
- *   avion_attn_bwd_dq   : query-stationary pass.  Computes the row sums delta = rowsum(dO o O) into
- *                         `workspace`, and dQ = scale * (P o (dO V^T - delta)) K.  Writes dq (fully)
- *                         and the workspace.
- *   avion_attn_bwd_dkdv : key-stationary pass.  Reads delta from `workspace` (as left there by
- *                         avion_attn_bwd_dq for the same q, k, v, o, lse, dO) and computes
- *                         dV = P^T dO and dK = scale * dS^T Q.  Writes dk, dv (fully).
+ *   avion_attn_bwd_dq   : query-stationary pass.  Computes the row sums delta = rowsum(dO o O) and
+ *                         dQ = scale * (P o (dO V^T - delta)) K.  Writes dq (fully) and leaves
+ *                         delta and lse, in the form the second pass consumes, in `workspace`.
+ *   avion_attn_bwd_dkdv : key-stationary pass.  Reads delta and lse from `workspace` (as left there
+ *                         by avion_attn_bwd_dq for the same q, k, v, o, lse, dO; the `lse` argument
+ *                         is only checked) and computes dV = P^T dO and dK = scale * dS^T Q.
+ *                         Writes dk, dv (fully).
  * Both rebuild P from q, k and lse block by block (Sec. 3: the weights stay implicit).
  */
 int avion_attn_bwd_dq(const void *q, const void *k, const void *v, const void *o, const float *lse,

@@ -31,8 +31,9 @@ int check_shape(int B, int H, int N, int d, float scale)
     if (!(scale > 0.f) || !std::isfinite(scale)) return AVION_EINVAL;
     if (d != 64 && d != 80) return AVION_EUNSUPPORTED;
     if (N > (1 << 24) || (long long)B * H > (1 << 24)) return AVION_EUNSUPPORTED;
-    // one (batch, head) slice is addressed with 32-bit byte offsets (buffer loads)
-    if ((long long)N * H * d * 2 >= (1LL << 31)) return AVION_EUNSUPPORTED;
+    // one (batch, head) slice is addressed with 32-bit byte offsets (buffer loads), and tile loads
+    // may start up to four 64-row tiles past the end of the sequence
+    if (((long long)N + 256) * H * d * 2 >= (1LL << 31)) return AVION_EUNSUPPORTED;
     return AVION_OK;
 }
 
@@ -95,8 +96,8 @@ int launch_dq(const bf16* q, const bf16* k, const bf16* v, const bf16* o, const 
 }
 
 template <int D, int NW>
-int launch_dkdv(const bf16* q, const bf16* k, const bf16* v, const bf16* dO, const float* lse, const float* delta,
-                bf16* dk, bf16* dv, int B, int H, int N, float scale, hipStream_t st)
+int launch_dkdv(const bf16* q, const bf16* k, const bf16* v, const bf16* dO, const float* rowsc, bf16* dk, bf16* dv,
+                int B, int H, int N, float scale, hipStream_t st)
 {
     using Cfg = DkvCfg<D, NW>;
     static hipError_t attr = allow_lds(avion_dkdv_kernel<D, NW>, Cfg::LDS_BYTES);
@@ -105,8 +106,8 @@ int launch_dkdv(const bf16* q, const bf16* k, const bf16* v, const bf16* dO, con
     const long long nblocks = (long long)nkb * B * H;
     unsigned grid;
     if (!grid_for(nblocks, &grid)) return AVION_EUNSUPPORTED;
-    hipLaunchKernelGGL((avion_dkdv_kernel<D, NW>), dim3(grid), dim3(Cfg::NT), Cfg::LDS_BYTES, st, q, k, v, dO, lse,
-                       delta, dk, dv, H, N, nkb, (int)nblocks, scale * kLog2e, scale);
+    hipLaunchKernelGGL((avion_dkdv_kernel<D, NW>), dim3(grid), dim3(Cfg::NT), Cfg::LDS_BYTES, st, q, k, v, dO, rowsc,
+                       dk, dv, H, N, nkb, (int)nblocks, scale * kLog2e, scale);
     const hipError_t e = hipGetLastError();
     return e == hipSuccess ? AVION_OK : hip_fail(e, "launch avion_dkdv_kernel");
 }
@@ -132,14 +133,14 @@ int dq_dispatch(const bf16* q, const bf16* k, const bf16* v, const bf16* o, cons
 }
 
 template <int D>
-int dkdv_dispatch(const bf16* q, const bf16* k, const bf16* v, const float* lse, const bf16* dO, bf16* dk, bf16* dv,
-                  const float* delta, int B, int H, int N, float scale, hipStream_t st)
+int dkdv_dispatch(const bf16* q, const bf16* k, const bf16* v, const bf16* dO, bf16* dk, bf16* dv, const float* rowsc,
+                  int B, int H, int N, float scale, hipStream_t st)
 {
     if constexpr (D == 64) {
         static const int vk = variant("DKDV", 0);
-        if (vk == 2) return launch_dkdv<D, 8>(q, k, v, dO, lse, delta, dk, dv, B, H, N, scale, st);
+        if (vk == 2) return launch_dkdv<D, 8>(q, k, v, dO, rowsc, dk, dv, B, H, N, scale, st);
     }
-    return launch_dkdv<D, 4>(q, k, v, dO, lse, delta, dk, dv, B, H, N, scale, st);
+    return launch_dkdv<D, 4>(q, k, v, dO, rowsc, dk, dv, B, H, N, scale, st);
 }
 
 bool workspace_ok(const void* workspace, size_t workspace_bytes, int B, int H, int N, int d)
@@ -185,7 +186,9 @@ int avion_attn_fwd(const void* q, const void* k, const void* v, void* o, float* 
 size_t avion_attn_bwd_workspace_bytes(int B, int H, int N, int d)
 {
     if (check_shape(B, H, N, d, 1.0f) != AVION_OK) return 0;
-    const size_t bytes = (size_t)B * H * N * sizeof(float);
+    // per (batch, head): LSE*log2e and -delta, each padded to a multiple of 64 rows
+    const size_t npad = ((size_t)N + 63) & ~(size_t)63;
+    const size_t bytes = (size_t)B * H * 2 * npad * sizeof(float);
     return (bytes + 255) & ~(size_t)255;
 }
 
@@ -221,12 +224,12 @@ int avion_attn_bwd_dkdv(const void* q, const void* k, const void* v, const float
         if (!aligned16(p)) return AVION_EUNSUPPORTED;
     if (!workspace_ok(workspace, workspace_bytes, B, H, N, d)) return AVION_EWORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const float* delta = static_cast<const float*>(workspace);
+    const float* rowsc = static_cast<const float*>(workspace);  // LSE*log2e and -delta, left by the dQ pass
     const bf16 *qq = static_cast<const bf16*>(q), *kk = static_cast<const bf16*>(k), *vv = static_cast<const bf16*>(v),
                *gg = static_cast<const bf16*>(dO);
     bf16 *dkk = static_cast<bf16*>(dk), *dvv = static_cast<bf16*>(dv);
-    if (d == 64) return dkdv_dispatch<64>(qq, kk, vv, lse, gg, dkk, dvv, delta, B, H, N, scale, st);
-    return dkdv_dispatch<80>(qq, kk, vv, lse, gg, dkk, dvv, delta, B, H, N, scale, st);
+    if (d == 64) return dkdv_dispatch<64>(qq, kk, vv, gg, dkk, dvv, rowsc, B, H, N, scale, st);
+    return dkdv_dispatch<80>(qq, kk, vv, gg, dkk, dvv, rowsc, B, H, N, scale, st);
 }
 
 int avion_attn_bwd(const void* q, const void* k, const void* v, const void* o, const float* lse, const void* dO,

@@ -33,7 +33,7 @@ template <int D, int QT, int NW>
 __global__ void __launch_bounds__(NW * 64)
 avion_dq_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v,
                 const bf16* __restrict__ o, const bf16* __restrict__ dO, const float* __restrict__ lse,
-                bf16* __restrict__ dq, float* __restrict__ delta, int H, int N, int nqb, int nblocks,
+                bf16* __restrict__ dq, float* __restrict__ rowsc, int H, int N, int nqb, int nblocks,
                 float cs, float scale)
 {
     using Cfg = DqCfg<D, QT, NW>;
@@ -76,7 +76,14 @@ avion_dq_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf
         }
         dl[qt] = both_halves_sum(part);
         lc[qt] = lse[(long)bh * N + row] * kLog2e;
-        if (wave_active && g == 0 && q0 + 32 * qt + l32 < N) delta[(long)bh * N + row] = dl[qt];
+        // per-query scalars for the dK/dV pass, in the form it consumes them: LSE*log2e and -delta,
+        // each array padded to a multiple of 64 rows with +inf (weight 0) and 0
+        const int qrow = q0 + 32 * qt + l32, npad = (N + 63) & ~63;
+        if (g == 0 && qrow < npad) {
+            float* ws = rowsc + (long)bh * 2 * npad;
+            ws[qrow] = qrow < N ? lc[qt] : INFINITY;
+            ws[npad + qrow] = qrow < N ? -dl[qt] : 0.f;
+        }
     }
 
     f32x16 acc[CT][QT];
@@ -188,10 +195,11 @@ avion_dq_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf
 
 // ------------------------------------------------------------------------------------------ dK, dV
 // One wavefront owns 32 keys; the workgroup's NW wavefronts share LDS tiles of BQ = 64 queries
-// (Q and dO rows, LSE*log2e and delta), four buffers deep.  Work is cut into units of 32 queries.
-// In program order every unit holds three independent strands that the scheduler is asked to
-// interleave instruction by instruction, because a wavefront issues in order and an MFMA that is
-// queued behind another one blocks everything after it:
+// (Q and dO rows, LSE*log2e and -delta), four buffers deep, filled straight from global memory by
+// LDS-direct loads (no staging registers, no LDS write instructions).  Work is cut into units of 32
+// queries.  In program order every unit holds three independent strands that are interleaved
+// instruction by instruction, because a wavefront issues in order and an MFMA that is queued behind
+// another one blocks everything after it:
 //   matrix cores : S and dP of the NEXT unit (into a second accumulator pair), and the dV^T, dK^T
 //                  updates of the PREVIOUS unit (from its saved bf16 P and dS fragments);
 //   vector ALUs  : P = exp2(cs*S - lc), dS = P o (dP - delta) of the CURRENT unit, rounded to bf16
@@ -203,7 +211,7 @@ struct DkvCfg {
     static constexpr int BNK = 32 * NW;  // keys per workgroup
     static constexpr int NBUF = 4;
     using Stage = TileStage<D, BQ, NT>;
-    static constexpr int ROWV_BYTES = 2 * BQ * 4;  // LSE*log2e and delta of the tile's queries
+    static constexpr int ROWV_BYTES = 1024;  // lc[BQ] | -delta[BQ] | unused: one 1 KB load
     static constexpr int BUF_BYTES = 2 * Stage::BYTES + ROWV_BYTES;
     static constexpr int LDS_BYTES = NBUF * BUF_BYTES;
 };
@@ -211,7 +219,7 @@ struct DkvCfg {
 template <int D, int NW>
 __global__ void __launch_bounds__(NW * 64)
 avion_dkdv_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v,
-                  const bf16* __restrict__ dO, const float* __restrict__ lse, const float* __restrict__ delta,
+                  const bf16* __restrict__ dO, const float* __restrict__ rowsc,
                   bf16* __restrict__ dk, bf16* __restrict__ dv, int H, int N, int nkb, int nblocks,
                   float cs, float scale)
 {
@@ -229,13 +237,16 @@ avion_dkdv_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const 
     if (logical < 0) return;
     const int bh = logical / nkb, kb = logical % nkb;
     const int b = bh / H, h = bh % H;
-    const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64, l32 = lane % 32, g = lane / 32;
+    const int tid = threadIdx.x, lane = tid % 64, l32 = lane % 32, g = lane / 32;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
     const long rs = (long)H * D;
     const long head_off = ((long)b * N * H + h) * D;
     const SliceView qh(q + head_off, rs, N, D);
     const SliceView gh(dO + head_off, rs, N, D);
-    const float* lrow = lse + (long)bh * N;
-    const float* drow = delta + (long)bh * N;
+    // per-query scalars as the dQ pass left them: lc[npad] = LSE*log2e, then -delta[npad]
+    const int npad = (N + 63) & ~63;
+    const RawBuffer rowsc_buf(rowsc + (long)bh * 2 * npad, 2 * npad * 4);
+    const RawBuffer q_buf(q + head_off, qh.bytes), g_buf(dO + head_off, gh.bytes);
     const int k0 = kb * BNK + wave * 32;  // first key of this wavefront
     const bool wave_active = k0 < N;
     const int tr_off = tr_lane_offset(lane, STRIDE);
@@ -259,47 +270,64 @@ avion_dkdv_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const 
         dva[ct] = f32x16_zero();
     }
 
-    Stage qst, gst;
-    float lc_r = 0.f, dl_r = 0.f;
-    constexpr int RPW = BQ / NW;  // per-query scalars staged by each wavefront
-    const int row_slot = wave * RPW + lane;
-    // The per-query scalars are fetched raw (row index clamped, no dependent arithmetic) so that
-    // nothing waits for them until the tile is written to LDS, one iteration later.
-    auto load_tile = [&](int r0) {
-        qst.load(qh, r0, tid);
-        gst.load(gh, r0, tid);
-        if (lane < RPW) {  // every wavefront fetches an equal share of the per-query scalars
-            const int tok = min(r0 + row_slot, N - 1);
-            lc_r = lrow[tok];
-            dl_r = drow[tok];
-        }
+    // Tile movement.  A tile buffer is a sequence of 1 KB blocks, each filled by one LDS-direct
+    // load of one wavefront: NTI blocks of Q rows, NTI of dO rows (row stride STRIDE, so a block
+    // holds 64 consecutive 16-byte chunks of the padded rows; lanes that land on a pad chunk fetch
+    // from beyond the buffer and deposit zeros), then one block with the 64 lc and 64 -delta values.
+    // Wavefront w issues blocks w, w+NW, ... of Q and of dO; the remaining blocks (the last of Q,
+    // the last of dO, the scalars) go one each to wavefronts 0, 1, 2, and further wavefronts repeat
+    // the scalars so that every wavefront issues the same number NPW of loads per tile.
+    constexpr int CPR = STRIDE / 16, DCH = D / 8;
+    static_assert(Stage::BYTES % 1024 == 0, "a tile must be a whole number of 1 KB blocks");
+    constexpr int NTI = Stage::BYTES / 1024, FULL = NTI / NW, REM = NTI % NW;
+    static_assert(REM == 1 && NW >= 3, "block distribution assumes one left-over block per tensor");
+    constexpr int NPW = 2 * FULL + 1;
+    const unsigned row_bytes = qh.row_bytes;
+    auto block_voff = [&](int blk) -> unsigned {  // offset of this lane's chunk of a Q / dO block
+        const int c = 64 * blk + lane, row = c / CPR, pos = c % CPR;
+        return pos < DCH ? (unsigned)row * row_bytes + pos * 16 : kOutOfRangeBase;
     };
-    auto store_tile = [&](char* buf, int r0) {
-        qst.store(buf, tid);
-        gst.store(buf + OFF_G, tid);
-        if (lane < RPW) {
-            const bool valid = r0 + row_slot < N;
-            // queries beyond N get weight exp2(-inf) = 0, hence dS = 0 as well; delta is stored
-            // negated because it seeds the dP accumulator
-            reinterpret_cast<float*>(buf + OFF_ROW)[row_slot] = valid ? lc_r * kLog2e : INFINITY;
-            reinterpret_cast<float*>(buf + OFF_ROW)[BQ + row_slot] = valid ? -dl_r : 0.f;
-        }
-    };
-    if constexpr (D % 32 != 0) {
-        for (int i = 0; i < Cfg::NBUF; ++i) {
-            Stage::zero_pad(smem + i * Cfg::BUF_BYTES, tid);
-            Stage::zero_pad(smem + i * Cfg::BUF_BYTES + OFF_G, tid);
-        }
-    }
+    unsigned voff[FULL];
+#pragma unroll
+    for (int m = 0; m < FULL; ++m) voff[m] = block_voff(wave + NW * m);
+    const bool left_is_rows = wave < 2;  // wavefront 0: last Q block, 1: last dO block, else scalars
+    const unsigned left_voff = left_is_rows ? block_voff(NTI - 1)
+                               : lane < 16  ? (unsigned)lane * 16
+                               : lane < 32  ? (unsigned)(npad * 4 + (lane - 16) * 16)
+                                            : kOutOfRangeBase;
+    const unsigned left_step = left_is_rows ? BQ * row_bytes : BQ * 4;  // per tile
+    const RawBuffer left_buf = wave == 0 ? q_buf : wave == 1 ? g_buf : rowsc_buf;
+    const int left_lds = wave == 0 ? (NTI - 1) * 1024 : wave == 1 ? OFF_G + (NTI - 1) * 1024 : OFF_ROW;
+    const unsigned smem_addr = lds_address(smem);
     const int ntiles = (N + BQ - 1) / BQ;
-    load_tile(0);
-    store_tile(tilebuf(0), 0);
-    if (ntiles > 1) {
-        load_tile(BQ);
-        store_tile(tilebuf(1), BQ);
-    }
-    if (ntiles > 2) load_tile(2 * BQ);
-    __syncthreads();
+    // load j (0 <= j < NPW) of this wavefront for tile `ti`; tiles past the end arrive as zeros
+    auto fetch = [&](int ti, int j) {
+        const unsigned buf = smem_addr + (ti & 3) * Cfg::BUF_BYTES;
+        const unsigned base = (unsigned)ti * BQ * row_bytes;
+        if (j < FULL) load_to_lds16(q_buf, buf + (wave + NW * j) * 1024, voff[j] + base);
+        else if (j < 2 * FULL) load_to_lds16(g_buf, buf + OFF_G + (wave + NW * (j - FULL)) * 1024, voff[j - FULL] + base);
+        else {
+            const unsigned off = left_voff + (unsigned)ti * left_step;
+            load_to_lds16(left_buf, buf + left_lds, (left_is_rows || ti < ntiles) ? off : kOutOfRangeBase);
+        }
+    };
+    auto fetch_tile = [&](int ti) {
+#pragma unroll
+        for (int j = 0; j < NPW; ++j) fetch(ti, j);
+    };
+    // Wait until at most one tile's worth of this wavefront's loads is still in flight, then meet
+    // the other wavefronts: after it, every tile but the most recently requested one is in LDS.
+    // (Plain instructions instead of __syncthreads(): its fences would wait for ALL loads.)
+    auto tiles_landed_barrier = [&](auto drain_lds) {
+        if constexpr (decltype(drain_lds)::value)
+            asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(NPW) : "memory");
+        else
+            asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(NPW) : "memory");
+    };
+    fetch_tile(0);
+    fetch_tile(1);
+    fetch_tile(2);
+    tiles_landed_barrier(std::true_type{});
 
     // S and dP of one unit: rows = 32 queries (half hq of the tile), cols = this wave's 32 keys
     // -delta of the 16 queries this lane's accumulator registers belong to (broadcast LDS reads);
@@ -361,29 +389,58 @@ avion_dkdv_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const 
         return p;
     }();
     constexpr int LA = 3;  // LDS fragment reads run this many MFMAs ahead of their use
+    static_assert(NPW + 2 <= NM, "the tile loads must fit the MFMA slots of a unit");
+    // Slot of the first unit of an iteration after which the wavefronts synchronise.  Before it, all
+    // reads of the PREVIOUS tile (dV, dK operands) must have returned, because the next loads
+    // overwrite that tile; after it come the first reads of the NEXT tile (the S operand fetched
+    // LA slots ahead for the following unit), because only then is it complete.
+    constexpr int LAST_PREV_SLOT = [] {
+        int last = 0;
+        for (int i = 0; i < NM; ++i)
+            if (plan.kind[i] <= 1) last = i;
+        return last;
+    }();
+    static_assert(LA >= 2 && plan.kind[0] <= 1 && plan.kind[1] <= 1 && plan.kind[2] >= 2,
+                  "the first read of the next tile is the unit's third fragment");
+    constexpr int FIRST_NEXT_SLOT = NM - LA + 2;  // where the following unit's third fragment is requested
+    constexpr int SYNC_SLOT = LAST_PREV_SLOT < FIRST_NEXT_SLOT ? LAST_PREV_SLOT : FIRST_NEXT_SLOT - 1;
+    constexpr bool SYNC_DRAINS = LAST_PREV_SLOT > SYNC_SLOT;  // then outstanding LDS reads are waited for
+
+    // Which LDS buffers a unit reads: S, dP of the NEXT unit from (bnext, half hnext); LSE of the
+    // CURRENT unit from (bcur, hcur); dV, dK of the PREVIOUS unit from (bprev, hprev).
+    struct Where {
+        const char *bnext, *bcur, *bprev;
+        int hnext, hcur, hprev;
+    };
+    auto frag = [&](const Where& w, int i) -> bf16x8 {
+        const int kd = plan.kind[i], ar = plan.arg[i];
+        if (kd == 0) return tr_frag(w.bprev + OFF_G, STRIDE, tr_off, ar % CT, 2 * w.hprev + ar / CT);
+        if (kd == 1) return tr_frag(w.bprev, STRIDE, tr_off, ar % CT, 2 * w.hprev + ar / CT);
+        if (kd == 2) return nat_frag(w.bnext, STRIDE, 32 * w.hnext + l32, ar, g);
+        return nat_frag(w.bnext + OFF_G, STRIDE, 32 * w.hnext + l32, ar, g);
+    };
+    auto lse_rows = [&](const Where& w, int a4) -> f32x4 {
+        return *reinterpret_cast<const f32x4*>(reinterpret_cast<const float*>(w.bcur + OFF_ROW) + 32 * w.hcur + 4 * g + 8 * a4);
+    };
 
     // One unit.  cur = S, dP of the current unit (turned into P, dS in place), nxt = accumulators of
     // the next unit, *_p = bf16 fragments of the previous unit, *_c = those of the current one.
-    auto unit = [&](const char* bnext, int hnext, const char* bcur, int hcur, const char* bprev, int hprev,
-                    f32x16& s_c, f32x16& dp_c, f32x16& s_n, f32x16& dp_n, const u32x4 (&pf_p)[2],
-                    const u32x4 (&df_p)[2], u32x4 (&pf_c)[2], u32x4 (&df_c)[2]) {
-        auto frag = [&](int i) -> bf16x8 {
-            const int kd = plan.kind[i], ar = plan.arg[i];
-            if (kd == 0) return tr_frag(bprev + OFF_G, STRIDE, tr_off, ar % CT, 2 * hprev + ar / CT);
-            if (kd == 1) return tr_frag(bprev, STRIDE, tr_off, ar % CT, 2 * hprev + ar / CT);
-            if (kd == 2) return nat_frag(bnext, STRIDE, 32 * hnext + l32, ar, g);
-            return nat_frag(bnext + OFF_G, STRIDE, 32 * hnext + l32, ar, g);
-        };
-        const float* rowv = reinterpret_cast<const float*>(bcur + OFF_ROW) + 32 * hcur + 4 * g;
+    // `pre` and `l4pre` arrive holding the first LA fragments and the first four LSE values of this
+    // unit and leave holding those of the unit that follows (`wn`), so the LDS pipeline never
+    // drains between units.  side(j), j = 0 .. NPW-1, is called in slots 2, 3, ...: the tile loads.
+    auto unit = [&](auto sync, const Where& w, const Where& wn, f32x16& s_c, f32x16& dp_c, f32x16& s_n,
+                    f32x16& dp_n, const u32x4 (&pf_p)[2], const u32x4 (&df_p)[2], u32x4 (&pf_c)[2],
+                    u32x4 (&df_c)[2], bf16x8 (&pre)[LA], f32x4& l4pre, auto&& side) {
         bf16x8 fr[NM];
         f32x4 l4[4];
 #pragma unroll
-        for (int i = 0; i < LA; ++i) fr[i] = frag(i);
-        l4[0] = *reinterpret_cast<const f32x4*>(rowv);
-        dp_n = neg_delta_rows(bnext, hnext);
+        for (int i = 0; i < LA; ++i) fr[i] = pre[i];
+        l4[0] = l4pre;
+        dp_n = neg_delta_rows(w.bnext, w.hnext);
 #pragma unroll
         for (int i = 0; i < NM; ++i) {
-            if (i + LA < NM) fr[i + LA] = frag(i + LA);
+            if (i + LA < NM) fr[i + LA] = frag(w, i + LA);
+            else pre[i + LA - NM] = frag(wn, i + LA - NM);
             const int kd = plan.kind[i], ar = plan.arg[i];
             if (kd == 0) dva[ar % CT] = mfma32(fr[i], as_bf16x8(pf_p[ar / CT]), dva[ar % CT]);
             if (kd == 1) dka[ar % CT] = mfma32(fr[i], as_bf16x8(df_p[ar / CT]), dka[ar % CT]);
@@ -393,8 +450,7 @@ avion_dkdv_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const 
             const int e0 = i * 16 / NM, e1 = (i + 1) * 16 / NM;
 #pragma unroll
             for (int e = e0; e < e1; ++e) {
-                if (e % 4 == 0 && e + 4 < 16)  // LSE*log2e of the next four queries
-                    l4[e / 4 + 1] = *reinterpret_cast<const f32x4*>(rowv + 8 * (e / 4 + 1));
+                if (e % 4 == 0 && e + 4 < 16) l4[e / 4 + 1] = lse_rows(w, e / 4 + 1);  // next four queries
                 const float pe = fast_exp2(fmaf(s_c[e], cs, -l4[e / 4][e % 4]));
                 s_c[e] = pe;
                 dp_c[e] = pe * dp_c[e];  // dp_c already holds dP - delta
@@ -403,6 +459,9 @@ avion_dkdv_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const 
                     df_c[e / 8][(e / 2) % 4] = pack_bf16(dp_c[e - 1], dp_c[e]);
                 }
             }
+            if (i == NM - 1) l4pre = lse_rows(wn, 0);
+            if (i >= 2 && i - 2 < NPW) side(i - 2);
+            if (decltype(sync)::value && i == SYNC_SLOT) tiles_landed_barrier(std::bool_constant<SYNC_DRAINS>{});
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -417,28 +476,39 @@ avion_dkdv_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const 
     if (wave_active) scores(tilebuf(0), 0, sA, dpA);
     wait_all_loads();
 
-    // Tile t+2 travels through registers: fetched during iteration t-1, written to LDS between the
-    // two units of iteration t (its buffer held tile t-2, which nobody reads after the barrier that
-    // ended iteration t-1), first read after the barrier that ends iteration t.  Neither the global
-    // loads nor the LDS writes are waited for at the barrier itself.
+    // Unit 2t (first query half of tile t) and unit 2t+1 (second half).  One synchronisation per
+    // iteration, inside unit 2t: it certifies that tile t+1 is complete (first read right after it)
+    // and that nobody reads tile t-1 any more, whose buffer the loads of tile t+3, issued during
+    // unit 2t+1, overwrite.  A tile therefore has one and a half iterations to arrive.
+    auto where_a = [&](int t) {  // unit 2t: previous = second half of tile t-1 (zero weights at t = 0)
+        return Where{tilebuf(t), tilebuf(t), tilebuf(t - 1 < 0 ? 0 : t - 1), 1, 0, 1};
+    };
+    auto where_b = [&](int t) {  // unit 2t+1: next = first half of tile t+1
+        return Where{tilebuf(t + 1), tilebuf(t), tilebuf(t), 0, 1, 0};
+    };
+    bf16x8 pre[LA];
+    f32x4 l4pre;
+    {
+        const Where w0 = where_a(0);
+#pragma unroll
+        for (int i = 0; i < LA; ++i) pre[i] = frag(w0, i);
+        l4pre = lse_rows(w0, 0);
+    }
     for (int t = 0; t < ntiles; ++t) {
-        const char* bprev = tilebuf(t - 1 < 0 ? 0 : t - 1);
-        const char* bcur = tilebuf(t);
-        const char* bnext = tilebuf(t + 1);
-        // unit 2t: current = A; next = unit 2t+1 (same tile, second half); previous = unit 2t-1
-        // (second half of tile t-1; at t = 0 its fragments are zero)
-        if (wave_active) unit(bcur, 1, bcur, 0, bprev, 1, sA, dpA, sB, dpB, pfB, dfB, pfA, dfA);
-        if (t + 2 < ntiles) store_tile(tilebuf(t + 2), (t + 2) * BQ);
-        if (t + 3 < ntiles) load_tile((t + 3) * BQ);
-        __builtin_amdgcn_sched_barrier(0);
-        // unit 2t+1: current = B; next = unit 2t+2 (first half of tile t+1; past the last tile
-        // this reads a stale buffer whose result is never used); previous = unit 2t
-        if (wave_active) unit(bnext, 0, bcur, 1, bcur, 0, sB, dpB, sA, dpA, pfA, dfA, pfB, dfB);
-        __syncthreads();
+        const Where wa = where_a(t), wb = where_b(t), wa1 = where_a(t + 1);
+        auto next_tile = [&](int j) { fetch(t + 3, j); };
+        if (wave_active) {
+            unit(std::true_type{}, wa, wb, sA, dpA, sB, dpB, pfB, dfB, pfA, dfA, pre, l4pre, [](int) {});
+            unit(std::false_type{}, wb, wa1, sB, dpB, sA, dpA, pfA, dfA, pfB, dfB, pre, l4pre, next_tile);
+        } else {
+            tiles_landed_barrier(std::false_type{});
+            fetch_tile(t + 3);
+        }
     }
 
     if (wave_active) accumulate(tilebuf(ntiles - 1), 1, pfB, dfB);  // the last unit's contribution
-    __syncthreads();  // all tile reads are done: the buffers now stage the output rows
+    wait_all_loads();  // zero tiles requested past the end must have landed before LDS is reused
+    __syncthreads();   // all tile reads are done: the buffers now stage the output rows
     if (!wave_active) return;
     char* region = smem + wave * RowStore<D>::BYTES;
     RowStore<D>::run(region, dka, scale, dk + head_off + (long)k0 * rs, rs, N - k0, lane);

@@ -156,9 +156,10 @@ DEVINL float frag_sum(bf16x8 f, float acc)
 struct SliceView {
     __amdgpu_buffer_rsrc_t rsrc;
     unsigned row_bytes;  // rs * 2
+    unsigned bytes;      // extent of the slice
     DEVINL SliceView(const bf16* base, long rs, int N, int D)
     {
-        const unsigned bytes = (unsigned)(((long)(N - 1) * rs + D) * 2);
+        bytes = (unsigned)(((long)(N - 1) * rs + D) * 2);
         rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16*>(base), 0, (int)bytes, 0x00020000);
         row_bytes = (unsigned)(rs * 2);
     }
@@ -166,6 +167,36 @@ struct SliceView {
     DEVINL u32x2 load8(unsigned byte_off) const { return __builtin_amdgcn_raw_buffer_load_b64(rsrc, byte_off, 0, 0); }
 };
 constexpr unsigned kOutOfRange = 0x7fffffffu;  // a byte offset no slice reaches
+// Same, for offsets that a tile base (< 2^31) is still added to: the sum stays in [2^31, 2^32).
+constexpr unsigned kOutOfRangeBase = 0x80000000u;
+
+// Global -> LDS without passing through registers (buffer_load_dwordx4 ... lds): the 16 bytes that
+// lane i fetches from byte offset `voff` of the buffer land at LDS address lds_addr + 16*i, so one
+// instruction fills 1 KB of LDS; lds_addr (it travels in M0) must be the same in all lanes.
+// Offsets beyond the buffer deposit zeros.  Completion is tracked by the vector-memory counter
+// (s_waitcnt vmcnt), like any other load.
+// Written as inline assembly on purpose: told that an instruction writes LDS asynchronously, the
+// compiler makes every later LDS read wait for ALL outstanding loads, which would serialise the
+// prefetch; here the ordering is established by hand (vmcnt waits + workgroup barriers).
+struct RawBuffer {
+    u32x4 words;  // base[31:0] | base[47:32] | bytes | flags: raw buffer, offsets beyond `bytes` are out of range
+    DEVINL RawBuffer(const void* base, unsigned bytes)
+    {
+        const unsigned long a = (unsigned long)base;
+        words[0] = __builtin_amdgcn_readfirstlane((unsigned)a);
+        words[1] = __builtin_amdgcn_readfirstlane((unsigned)(a >> 32) & 0xffffu);
+        words[2] = __builtin_amdgcn_readfirstlane(bytes);
+        words[3] = 0x00020000u;
+    }
+};
+DEVINL unsigned lds_address(const char* p) { return (unsigned)(unsigned long)(const lds_char*)p; }
+DEVINL void load_to_lds16(const RawBuffer& buf, unsigned lds_addr, unsigned voff)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :
+                 : "s"(lds_addr), "v"(voff), "s"(buf.words)
+                 : "memory", "m0");
+}
 
 // row stride of an LDS tile in bytes
 template <int D>
@@ -211,25 +242,30 @@ struct TileStage {
     static constexpr int BYTES = R * STRIDE;
     u32x4 r[PER];
 
+    // piece i (0 <= i < PER) of the tile: one 16-byte load / store per thread
+    DEVINL void load_piece(const SliceView& src, int r0, int tid, int i)
+    {
+        const int idx = tid + i * NT;
+        const int row = idx / CH, ch = idx % CH;
+        unsigned off = (unsigned)(r0 + row) * src.row_bytes + ch * 16;
+        if (TOTAL % NT != 0 && idx >= TOTAL) off = kOutOfRange;
+        r[i] = src.load16(off);
+    }
+    DEVINL void store_piece(char* tile, int tid, int i) const
+    {
+        const int idx = tid + i * NT;
+        const int row = idx / CH, ch = idx % CH;
+        if (TOTAL % NT == 0 || idx < TOTAL) *reinterpret_cast<u32x4*>(tile + row * STRIDE + ch * 16) = r[i];
+    }
     DEVINL void load(const SliceView& src, int r0, int tid)
     {
 #pragma unroll
-        for (int i = 0; i < PER; ++i) {
-            const int idx = tid + i * NT;
-            const int row = idx / CH, ch = idx % CH;
-            unsigned off = (unsigned)(r0 + row) * src.row_bytes + ch * 16;
-            if (TOTAL % NT != 0 && idx >= TOTAL) off = kOutOfRange;
-            r[i] = src.load16(off);
-        }
+        for (int i = 0; i < PER; ++i) load_piece(src, r0, tid, i);
     }
     DEVINL void store(char* tile, int tid) const
     {
 #pragma unroll
-        for (int i = 0; i < PER; ++i) {
-            const int idx = tid + i * NT;
-            const int row = idx / CH, ch = idx % CH;
-            if (TOTAL % NT == 0 || idx < TOTAL) *reinterpret_cast<u32x4*>(tile + row * STRIDE + ch * 16) = r[i];
-        }
+        for (int i = 0; i < PER; ++i) store_piece(tile, tid, i);
     }
     // the pad of every row reads as zeros (only D = 80 ever reads it)
     DEVINL static void zero_pad(char* tile, int tid)
