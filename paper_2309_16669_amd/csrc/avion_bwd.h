@@ -277,16 +277,12 @@ avion_dkdv_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const 
     // Wavefront w issues blocks w, w+NW, ... of Q and of dO; the remaining blocks (the last of Q,
     // the last of dO, the scalars) go one each to wavefronts 0, 1, 2, and further wavefronts repeat
     // the scalars so that every wavefront issues the same number NPW of loads per tile.
-    constexpr int CPR = STRIDE / 16, DCH = D / 8;
     static_assert(Stage::BYTES % 1024 == 0, "a tile must be a whole number of 1 KB blocks");
     constexpr int NTI = Stage::BYTES / 1024, FULL = NTI / NW, REM = NTI % NW;
     static_assert(REM == 1 && NW >= 3, "block distribution assumes one left-over block per tensor");
     constexpr int NPW = 2 * FULL + 1;
     const unsigned row_bytes = qh.row_bytes;
-    auto block_voff = [&](int blk) -> unsigned {  // offset of this lane's chunk of a Q / dO block
-        const int c = 64 * blk + lane, row = c / CPR, pos = c % CPR;
-        return pos < DCH ? (unsigned)row * row_bytes + pos * 16 : kOutOfRangeBase;
-    };
+    auto block_voff = [&](int blk) { return padded_block_voff<D>(blk, lane, row_bytes); };
     unsigned voff[FULL];
 #pragma unroll
     for (int m = 0; m < FULL; ++m) voff[m] = block_voff(wave + NW * m);

@@ -198,11 +198,26 @@ DEVINL void load_to_lds16(const RawBuffer& buf, unsigned lds_addr, unsigned voff
                  : "memory", "m0");
 }
 
+// Byte offset, relative to the tile's first row, that `lane` fetches for 1 KB block `blk` of a padded
+// LDS tile (row stride tile_stride<D>(), D/8 data chunks of 16 bytes per row, the rest padding): the
+// block holds chunks 64*blk .. 64*blk+63 of the tile in row-major order.  Lanes that land on a pad
+// chunk get an offset beyond any buffer, so that zeros are deposited there.
+template <int D>
+DEVINL unsigned padded_block_voff(int blk, int lane, unsigned row_bytes);
+
 // row stride of an LDS tile in bytes
 template <int D>
 constexpr int tile_stride()
 {
     return D == 64 ? 144 : D * 2 + 48;
+}
+
+template <int D>
+DEVINL unsigned padded_block_voff(int blk, int lane, unsigned row_bytes)
+{
+    constexpr int CPR = tile_stride<D>() / 16, DCH = D / 8;
+    const int c = 64 * blk + lane, row = c / CPR, pos = c % CPR;
+    return pos < DCH ? (unsigned)row * row_bytes + pos * 16 : kOutOfRangeBase;
 }
 
 // natural fragment: row `row`, 16-deep channel step `step`, lane group g

@@ -6,7 +6,8 @@
 // Each wavefront owns 32*QT queries and keeps, per query tile of 32:
 //   Q as MFMA B-operand fragments (lane = query, 8 channels per 16-deep step),
 //   O^T accumulators (lane = query, registers = channels), the reference maximum and row sums.
-// Keys and values come in LDS tiles of 64 tokens in their natural row layout, four buffers deep:
+// Keys and values come in LDS tiles of 64 tokens in their natural row layout, four buffers deep,
+// filled straight from global memory by LDS-direct loads (no staging registers, no LDS writes):
 // K rows are the A operand of S^T = K Q^T, and V is read through transposing LDS loads as the A
 // operand of O^T = V^T P^T.  Computing the transposed products keeps every score of a query inside
 // one lane pair, so the accumulator of the first contraction is, after rounding to bf16, directly
@@ -63,7 +64,12 @@ DEVINL void avion_fwd_safe_pass(char* smem, const SliceView& kh, const SliceView
         for (int ct = 0; ct < CT; ++ct) oacc[ct][qt] = f32x16_zero();
     }
     Stage kst, vst;
+    wait_all_loads();  // tiles the main loop requested past the end must have landed
     __syncthreads();
+    if constexpr (D % 32 != 0) {
+        Stage::zero_pad(vbuf(0), tid);
+        Stage::zero_pad(vbuf(1), tid);
+    }
     kst.load(kh, 0, tid);
     vst.load(vh, 0, tid);
     kst.store(kbuf(0), tid);
@@ -158,7 +164,8 @@ avion_fwd_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const b
     if (logical < 0) return;
     const int bh = logical / nqb, qb = logical % nqb;
     const int b = bh / H, h = bh % H;
-    const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64, l32 = lane % 32, g = lane / 32;
+    const int tid = threadIdx.x, lane = tid % 64, l32 = lane % 32, g = lane / 32;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
     const long rs = (long)H * D;
     const long head_off = ((long)b * N * H + h) * D;
     const bf16* qh = q + head_off;
@@ -190,25 +197,51 @@ avion_fwd_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const b
         for (int ct = 0; ct < CT; ++ct) oacc[ct][qt] = f32x16_zero();
     }
 
-    // Tiles travel global -> registers -> LDS.  Two register sets alternate so that a tile has
-    // two full steps to arrive: tile t+3 is requested at the start of step t and written to LDS
-    // at the end of step t+1.
+    // Tile movement.  A tile buffer is a sequence of 1 KB blocks, each filled by one LDS-direct
+    // load of one wavefront (row stride STRIDE, so a block holds 64 consecutive 16-byte chunks of
+    // the padded rows; lanes that land on a pad chunk deposit zeros).  Wavefront w issues blocks
+    // w, w+NW, ... of the K tile and of the V tile; the one left-over block of each goes to
+    // wavefronts 0 and 1, and further wavefronts repeat the V one, so that every wavefront issues
+    // the same number NPW of loads per tile pair.
     const int ntiles = (N + BN - 1) / BN;
-    Stage kst[2], vst[2];
-    if constexpr (D % 32 != 0) {
-        for (int i = 0; i < Cfg::NBUF; ++i) Stage::zero_pad(vbuf(i), tid);
-    }
-    kst[0].load(kh, 0, tid);
-    vst[0].load(vh, 0, tid);
-    kst[0].store(kbuf(0), tid);
-    vst[0].store(vbuf(0), tid);
-    if (ntiles > 1) {
-        kst[0].load(kh, BN, tid);
-        vst[0].load(vh, BN, tid);
-        kst[0].store(kbuf(1), tid);
-        vst[0].store(vbuf(1), tid);
-    }
-    __syncthreads();
+    static_assert(Stage::BYTES % 1024 == 0, "a tile must be a whole number of 1 KB blocks");
+    constexpr int NTI = Stage::BYTES / 1024, FULL = NTI / NW, REM = NTI % NW;
+    static_assert(REM == 1 && NW >= 2, "block distribution assumes one left-over block per tensor");
+    constexpr int NPW = 2 * FULL + 1;
+    const unsigned row_bytes = kh.row_bytes;
+    const RawBuffer k_buf(k + head_off, kh.bytes), v_buf(v + head_off, vh.bytes);
+    unsigned voff[FULL];
+#pragma unroll
+    for (int m = 0; m < FULL; ++m) voff[m] = padded_block_voff<D>(wave + NW * m, lane, row_bytes);
+    const unsigned left_voff = padded_block_voff<D>(NTI - 1, lane, row_bytes);
+    const RawBuffer left_buf = wave == 0 ? k_buf : v_buf;
+    const int left_lds = (wave == 0 ? 0 : 4 * Stage::BYTES) + (NTI - 1) * 1024;
+    const unsigned smem_addr = lds_address(smem);
+    // load j (0 <= j < NPW) of this wavefront for tile pair `ti`; tiles past the end arrive as zeros
+    auto fetch = [&](int ti, int j) {
+        const unsigned kb = smem_addr + (ti & 3) * Stage::BYTES, vb = kb + 4 * Stage::BYTES;
+        const unsigned base = (unsigned)ti * BN * row_bytes;
+        if (j < FULL) load_to_lds16(k_buf, kb + (wave + NW * j) * 1024, voff[j] + base);
+        else if (j < 2 * FULL) load_to_lds16(v_buf, vb + (wave + NW * (j - FULL)) * 1024, voff[j - FULL] + base);
+        else load_to_lds16(left_buf, kb + left_lds, left_voff + base);
+    };
+    auto fetch_tile = [&](int ti) {
+#pragma unroll
+        for (int j = 0; j < NPW; ++j) fetch(ti, j);
+    };
+    // Wait until at most one tile pair's worth of this wavefront's loads is still in flight, then
+    // meet the other wavefronts: after it, every tile but the most recently requested one is in
+    // LDS.  (Plain instructions instead of __syncthreads(): its fences would wait for ALL loads.)
+    auto tiles_landed_barrier = [&](auto drain_lds) {
+        if constexpr (decltype(drain_lds)::value)
+            asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(NPW) : "memory");
+        else
+            asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(NPW) : "memory");
+    };
+    fetch_tile(0);
+    fetch_tile(1);
+    fetch_tile(2);
+    tiles_landed_barrier(std::true_type{});
 
     // MFMAs of one unit in issue order: groups of QT sharing one LDS fragment; groups of the
     // previous unit's P V update (kind 0, arg = half*CT+ct) alternate with groups of the next
@@ -228,15 +261,41 @@ avion_fwd_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const b
     }();
     constexpr int LA = 2;  // fragment reads run this many groups ahead
     constexpr int NE = 16 * QT;    // score elements per lane and unit
+    static_assert(NPW + 2 <= NG, "the tile loads must fit the MFMA groups of a unit");
+    // Group of the first unit of an iteration after which the wavefronts synchronise.  Before it,
+    // all reads of the PREVIOUS V tile must have returned, because the next loads overwrite that
+    // tile pair; after it come the first reads of the NEXT K tile (requested LA groups ahead for
+    // the following unit), because only then is it complete.
+    static_assert(LA >= 1 && plan.kind[0] == 0 && plan.kind[1] == 1, "the first read of the next tile is the unit's second fragment");
+    constexpr int LAST_PREV_GROUP = [] {
+        int last = 0;
+        for (int i = 0; i < NG; ++i)
+            if (plan.kind[i] == 0) last = i;
+        return last;
+    }();
+    constexpr int FIRST_NEXT_GROUP = NG - LA + 1;
+    constexpr int SYNC_GROUP = LAST_PREV_GROUP < FIRST_NEXT_GROUP ? LAST_PREV_GROUP : FIRST_NEXT_GROUP - 1;
+    constexpr bool SYNC_DRAINS = LAST_PREV_GROUP > SYNC_GROUP;  // then outstanding LDS reads are waited for
 
-    // One unit: MASKED units replace scores of keys at or beyond N by -inf first.
-    auto unit = [&](auto masked, int key_base, const char* knext, int hnext, const char* vprev, int hprev,
-                    f32x16 (&s_c)[QT], f32x16 (&s_n)[QT], const u32x4 (&pf_p)[QT][2], u32x4 (&pf_c)[QT][2]) {
-        auto frag = [&](int gi) -> bf16x8 {
-            const int kd = plan.kind[gi], ar = plan.arg[gi];
-            if (kd == 0) return tr_frag(vprev, STRIDE, tr_off, ar % CT, 2 * hprev + ar / CT);
-            return nat_frag(knext, STRIDE, 32 * hnext + l32, ar, g);
-        };
+    // Which LDS tiles a unit reads: S^T of the NEXT unit from (knext, half hnext), the P V update of
+    // the PREVIOUS unit from (vprev, half hprev).
+    struct Where {
+        const char *knext, *vprev;
+        int hnext, hprev;
+    };
+    auto frag = [&](const Where& w, int gi) -> bf16x8 {
+        const int kd = plan.kind[gi], ar = plan.arg[gi];
+        if (kd == 0) return tr_frag(w.vprev, STRIDE, tr_off, ar % CT, 2 * w.hprev + ar / CT);
+        return nat_frag(w.knext, STRIDE, 32 * w.hnext + l32, ar, g);
+    };
+
+    // One unit: MASKED units replace scores of keys at or beyond N by -inf first.  `pre` arrives
+    // holding the first LA fragments of this unit and leaves holding those of the unit that follows
+    // (`wn`), so the LDS pipeline never drains between units.  side(j), j = 0 .. NPW-1, is called in
+    // groups 2, 3, ...: the tile loads.
+    auto unit = [&](auto sync, auto masked, int key_base, const Where& w, const Where& wn, f32x16 (&s_c)[QT],
+                    f32x16 (&s_n)[QT], const u32x4 (&pf_p)[QT][2], u32x4 (&pf_c)[QT][2], bf16x8 (&pre)[LA],
+                    auto&& side) {
         if constexpr (decltype(masked)::value) {
             const int key0 = key_base + 4 * g;
 #pragma unroll
@@ -248,11 +307,12 @@ avion_fwd_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const b
         }
         bf16x8 fr[NG];
 #pragma unroll
-        for (int gi = 0; gi < LA; ++gi) fr[gi] = frag(gi);
+        for (int gi = 0; gi < LA; ++gi) fr[gi] = pre[gi];
         const bf16x2 ones = {(bf16)1.0f, (bf16)1.0f};
 #pragma unroll
         for (int gi = 0; gi < NG; ++gi) {
-            if (gi + LA < NG) fr[gi + LA] = frag(gi + LA);
+            if (gi + LA < NG) fr[gi + LA] = frag(w, gi + LA);
+            else pre[gi + LA - NG] = frag(wn, gi + LA - NG);
             const int kd = plan.kind[gi], ar = plan.arg[gi];
 #pragma unroll
             for (int qt = 0; qt < QT; ++qt) {
@@ -272,10 +332,14 @@ avion_fwd_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const b
                     if (i % 2 == 1) {
                         // the second row sum runs over the weights as rounded to bf16, i.e. the
                         // numbers the second contraction multiplies V with; O is divided by it
-                        const unsigned w = pack_bf16(s_c[eq][i - 1], p);
-                        pf_c[eq][i / 8][(i / 2) % 4] = w;
-                        rsum[eq] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), ones, rsum[eq], false);
+                        const unsigned wgt = pack_bf16(s_c[eq][i - 1], p);
+                        pf_c[eq][i / 8][(i / 2) % 4] = wgt;
+                        rsum[eq] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, wgt), ones, rsum[eq], false);
                     }
+                }
+                if (qt == QT - 1) {
+                    if (gi >= 2 && gi - 2 < NPW) side(gi - 2);
+                    if (decltype(sync)::value && gi == SYNC_GROUP) tiles_landed_barrier(std::bool_constant<SYNC_DRAINS>{});
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -320,41 +384,39 @@ avion_fwd_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const b
         }
     }
     wait_all_loads();
-    if (ntiles > 2) {
-        kst[0].load(kh, 2 * BN, tid);
-        vst[0].load(vh, 2 * BN, tid);
-    }
 
-    // one step = one 64-key tile = two units; `in` receives tile t+3, `out` holds tile t+2
-    auto step = [&](int t, Stage& k_in, Stage& v_in, const Stage& k_out, const Stage& v_out) {
-        if (t + 3 < ntiles) {
-            k_in.load(kh, (t + 3) * BN, tid);
-            v_in.load(vh, (t + 3) * BN, tid);
-        }
+    // One step = one 64-key tile = two units.  Unit 2t: current = A; next = unit 2t+1 (K tile t,
+    // second half); previous = unit 2t-1 (V tile t-1, second half; at t = 0 its weights are zero
+    // and V tile 0 stands in).  Unit 2t+1: current = B; next = unit 2t+2 (K tile t+1, first half;
+    // past the last tile a zero tile whose scores are never used); previous = unit 2t (V tile t,
+    // first half).  One synchronisation per step, inside unit 2t: it certifies that tile pair t+1
+    // is complete (first read right after it) and that nobody reads pair t-1 any more, whose
+    // buffers the loads of pair t+3, issued during unit 2t+1, overwrite.  A tile therefore has one
+    // and a half steps to arrive.
+    auto where_a = [&](int t) { return Where{kbuf(t), vbuf(t - 1 < 0 ? 0 : t - 1), 1, 1}; };
+    auto where_b = [&](int t) { return Where{kbuf(t + 1), vbuf(t), 0, 0}; };
+    bf16x8 pre[LA];
+    {
+        const Where w0 = where_a(0);
+#pragma unroll
+        for (int gi = 0; gi < LA; ++gi) pre[gi] = frag(w0, gi);
+    }
+    for (int t = 0; t < ntiles; ++t) {
+        const Where wa = where_a(t), wb = where_b(t), wa1 = where_a(t + 1);
+        auto next_tile = [&](int j) { fetch(t + 3, j); };
+        auto nothing = [](int) {};
         if (wave_active) {
-            const char* vprev = vbuf(t - 1 < 0 ? 0 : t - 1);
-            __builtin_amdgcn_sched_barrier(0);
-            // unit 2t: current = A; next = unit 2t+1 (K tile t, second half); previous = unit 2t-1
-            // (V tile t-1, second half; at t = 0 its weights are zero and V tile 0 stands in)
-            // unit 2t+1: current = B; next = unit 2t+2 (K tile t+1, first half; past the last tile a
-            // stale buffer whose scores are never used); previous = unit 2t (V tile t, first half)
             if ((t + 1) * BN > N) {
-                unit(std::true_type{}, t * BN, kbuf(t), 1, vprev, 1, sA, sB, pfB, pfA);
-                unit(std::true_type{}, t * BN + 32, kbuf(t + 1), 0, vbuf(t), 0, sB, sA, pfA, pfB);
+                unit(std::true_type{}, std::true_type{}, t * BN, wa, wb, sA, sB, pfB, pfA, pre, nothing);
+                unit(std::false_type{}, std::true_type{}, t * BN + 32, wb, wa1, sB, sA, pfA, pfB, pre, next_tile);
             } else {
-                unit(std::false_type{}, 0, kbuf(t), 1, vprev, 1, sA, sB, pfB, pfA);
-                unit(std::false_type{}, 0, kbuf(t + 1), 0, vbuf(t), 0, sB, sA, pfA, pfB);
+                unit(std::true_type{}, std::false_type{}, 0, wa, wb, sA, sB, pfB, pfA, pre, nothing);
+                unit(std::false_type{}, std::false_type{}, 0, wb, wa1, sB, sA, pfA, pfB, pre, next_tile);
             }
+        } else {
+            tiles_landed_barrier(std::false_type{});
+            fetch_tile(t + 3);
         }
-        if (t + 2 < ntiles) {
-            k_out.store(kbuf(t + 2), tid);
-            v_out.store(vbuf(t + 2), tid);
-        }
-        __syncthreads();
-    };
-    for (int t = 0; t < ntiles; t += 2) {
-        step(t, kst[1], vst[1], kst[0], vst[0]);
-        if (t + 1 < ntiles) step(t + 1, kst[0], vst[0], kst[1], vst[1]);
     }
     if (wave_active) pv_only(vbuf(ntiles - 1), 1, pfB);
 
@@ -367,6 +429,7 @@ avion_fwd_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const b
             bad = bad || !(l <= kRowSumLimit);
         }
     }
+    wait_all_loads();  // zero tiles requested past the end must have landed before LDS is reused
     if (__syncthreads_or(bad ? 1 : 0))
         avion_fwd_safe_pass<D, QT, NW>(smem, kh, vh, qf, oacc, m_used, lsum, rsum, N, cs, wave_active, tid, l32, g, tr_off);
 
