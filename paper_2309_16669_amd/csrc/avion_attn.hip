@@ -78,19 +78,19 @@ int launch_fwd(const bf16* q, const bf16* k, const bf16* v, bf16* o, float* lse,
     return e == hipSuccess ? AVION_OK : hip_fail(e, "launch avion_fwd_kernel");
 }
 
-template <int D, int QT, int NW>
+template <int D, int NW>
 int launch_dq(const bf16* q, const bf16* k, const bf16* v, const bf16* o, const bf16* dO, const float* lse, bf16* dq,
-              float* delta, int B, int H, int N, float scale, hipStream_t st)
+              float* rowsc, int B, int H, int N, float scale, hipStream_t st)
 {
-    using Cfg = DqCfg<D, QT, NW>;
-    static hipError_t attr = allow_lds(avion_dq_kernel<D, QT, NW>, Cfg::LDS_BYTES);
+    using Cfg = DqCfg<D, NW>;
+    static hipError_t attr = allow_lds(avion_dq_kernel<D, NW>, Cfg::LDS_BYTES);
     if (attr != hipSuccess) return hip_fail(attr, "hipFuncSetAttribute(dq)");
     const int nqb = (N + Cfg::BM - 1) / Cfg::BM;
     const long long nblocks = (long long)nqb * B * H;
     unsigned grid;
     if (!grid_for(nblocks, &grid)) return AVION_EUNSUPPORTED;
-    hipLaunchKernelGGL((avion_dq_kernel<D, QT, NW>), dim3(grid), dim3(Cfg::NT), Cfg::LDS_BYTES, st, q, k, v, o, dO, lse,
-                       dq, delta, H, N, nqb, (int)nblocks, scale * kLog2e, scale);
+    hipLaunchKernelGGL((avion_dq_kernel<D, NW>), dim3(grid), dim3(Cfg::NT), Cfg::LDS_BYTES, st, q, k, v, o, dO, lse, dq,
+                       rowsc, H, N, nqb, (int)nblocks, scale * kLog2e, scale);
     const hipError_t e = hipGetLastError();
     return e == hipSuccess ? AVION_OK : hip_fail(e, "launch avion_dq_kernel");
 }
@@ -113,23 +113,23 @@ int launch_dkdv(const bf16* q, const bf16* k, const bf16* v, const bf16* dO, con
 }
 
 // Kernel instances.  Only instances that keep every array in registers (no scratch, no spills) are
-// dispatched; AVION_VARIANT_DQ / AVION_VARIANT_DKDV select the alternatives kept for tuning sweeps.
+// dispatched; AVION_VARIANT_FWD / AVION_VARIANT_DKDV select the alternatives kept for tuning sweeps.
 template <int D>
 int fwd_dispatch(const bf16* q, const bf16* k, const bf16* v, bf16* o, float* lse, int B, int H, int N, float scale,
                  hipStream_t st)
 {
+    if constexpr (D == 64) {
+        static const int vf = variant("FWD", 0);
+        if (vf == 6) return launch_fwd<D, 1, 6>(q, k, v, o, lse, B, H, N, scale, st);
+    }
     return launch_fwd<D, 1, 4>(q, k, v, o, lse, B, H, N, scale, st);
 }
 
 template <int D>
 int dq_dispatch(const bf16* q, const bf16* k, const bf16* v, const bf16* o, const float* lse, const bf16* dO, bf16* dq,
-                float* delta, int B, int H, int N, float scale, hipStream_t st)
+                float* rowsc, int B, int H, int N, float scale, hipStream_t st)
 {
-    if constexpr (D == 64) {
-        static const int vq = variant("DQ", 0);
-        if (vq == 2) return launch_dq<D, 2, 4>(q, k, v, o, dO, lse, dq, delta, B, H, N, scale, st);
-    }
-    return launch_dq<D, 1, 4>(q, k, v, o, dO, lse, dq, delta, B, H, N, scale, st);
+    return launch_dq<D, 4>(q, k, v, o, dO, lse, dq, rowsc, B, H, N, scale, st);
 }
 
 template <int D>

@@ -20,177 +20,250 @@
 #include "avion_common.h"
 
 // --------------------------------------------------------------------------------------------- dQ
-template <int D, int QT, int NW>
+// One wavefront owns 32 queries (Q, dO as B-operand fragments, LSE and delta as per-lane scalars);
+// the workgroup's NW wavefronts share K/V tile pairs of 64 keys that stream through a ring of four
+// LDS buffers each, filled by LDS-direct loads.  Work is cut into units of 32 keys and pipelined
+// like the other two kernels: in program order a unit interleaves, instruction by instruction,
+//   matrix cores : S^T = K Q^T and dP^T = V dO^T of the NEXT unit (second accumulator pair; the dP
+//                  accumulator starts from -delta), and dQ^T += K^T dS^T of the PREVIOUS unit;
+//   vector ALUs  : P = exp2(cs*S - lc) and dS = P o (dP - delta) of the CURRENT unit, rounded to bf16.
+template <int D, int NW>
 struct DqCfg {
     static constexpr int BN = 64;
     static constexpr int NT = NW * 64;
-    static constexpr int BM = 32 * QT * NW;
-    using Stage = TileStage<D, BN, NT>;
-    static constexpr int LDS_BYTES = 4 * Stage::BYTES;  // K0 K1 V0 V1
+    static constexpr int BM = 32 * NW;
+    using Ring = PairRing<D, NW>;
+    static constexpr int LDS_BYTES = Ring::LDS_BYTES;
+    // wavefronts per SIMD the register budget is sized for: as many as LDS lets a compute unit hold
+    static constexpr int WAVES_PER_SIMD = (160 * 1024 / LDS_BYTES) * NW / 4;
 };
 
-template <int D, int QT, int NW>
-__global__ void __launch_bounds__(NW * 64)
+template <int D, int NW>
+__global__ void __launch_bounds__(NW * 64, (DqCfg<D, NW>::WAVES_PER_SIMD))
 avion_dq_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v,
                 const bf16* __restrict__ o, const bf16* __restrict__ dO, const float* __restrict__ lse,
                 bf16* __restrict__ dq, float* __restrict__ rowsc, int H, int N, int nqb, int nblocks,
                 float cs, float scale)
 {
-    using Cfg = DqCfg<D, QT, NW>;
-    using Stage = typename Cfg::Stage;
-    constexpr int BN = Cfg::BN, BM = Cfg::BM, STRIDE = Stage::STRIDE;
+    using Cfg = DqCfg<D, NW>;
+    using Ring = typename Cfg::Ring;
+    constexpr int BN = Cfg::BN, BM = Cfg::BM, STRIDE = Ring::STRIDE;
     constexpr int KS = D / 16;
     constexpr int CT = (D + 31) / 32;
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    auto kbuf = [&](int i) { return smem + i * Stage::BYTES; };
-    auto vbuf = [&](int i) { return smem + (2 + i) * Stage::BYTES; };
 
     const int logical = xcd_local_id(blockIdx.x, nblocks);
     if (logical < 0) return;
     const int bh = logical / nqb, qb = logical % nqb;
     const int b = bh / H, h = bh % H;
-    const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64, l32 = lane % 32, g = lane / 32;
+    const int tid = threadIdx.x, lane = tid % 64, l32 = lane % 32, g = lane / 32;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
     const long rs = (long)H * D;
     const long head_off = ((long)b * N * H + h) * D;
     const SliceView kh(k + head_off, rs, N, D);
-    const SliceView vh(v + head_off, rs, N, D);
-    const int q0 = qb * BM + wave * 32 * QT;
+    const int q0 = qb * BM + wave * 32;
     const bool wave_active = q0 < N;
     const int tr_off = tr_lane_offset(lane, STRIDE);
 
+    // K/V tile pairs: request the first three before anything else
+    const int ntiles = (N + BN - 1) / BN;
+    const Ring ring(k + head_off, v + head_off, kh.bytes, kh.row_bytes, smem, wave, lane);
+    ring.fetch_pair(0);
+    ring.fetch_pair(1);
+    ring.fetch_pair(2);
+
     // Q and dO fragments (B operands), delta and LSE per lane
-    bf16x8 qf[QT][KS], gf[QT][KS];
-    float lc[QT], dl[QT];
-#pragma unroll
-    for (int qt = 0; qt < QT; ++qt) {
-        const int row = min(q0 + 32 * qt + l32, N - 1);
+    bf16x8 qf[KS], gf[KS];
+    float lc, dl;
+    {
+        const int row = min(q0 + l32, N - 1);
         const long off = head_off + (long)row * rs + g * 8;
         float part = 0.f;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-            qf[qt][ks] = *reinterpret_cast<const bf16x8*>(q + off + ks * 16);
-            gf[qt][ks] = *reinterpret_cast<const bf16x8*>(dO + off + ks * 16);
+            qf[ks] = *reinterpret_cast<const bf16x8*>(q + off + ks * 16);
+            gf[ks] = *reinterpret_cast<const bf16x8*>(dO + off + ks * 16);
             const bf16x8 of = *reinterpret_cast<const bf16x8*>(o + off + ks * 16);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) part = fmaf((float)of[e], (float)gf[qt][ks][e], part);
+            for (int e = 0; e < 8; ++e) part = fmaf((float)of[e], (float)gf[ks][e], part);
         }
-        dl[qt] = both_halves_sum(part);
-        lc[qt] = lse[(long)bh * N + row] * kLog2e;
+        dl = both_halves_sum(part);
+        lc = lse[(long)bh * N + row] * kLog2e;
         // per-query scalars for the dK/dV pass, in the form it consumes them: LSE*log2e and -delta,
         // each array padded to a multiple of 64 rows with +inf (weight 0) and 0
-        const int qrow = q0 + 32 * qt + l32, npad = (N + 63) & ~63;
+        const int qrow = q0 + l32, npad = (N + 63) & ~63;
         if (g == 0 && qrow < npad) {
             float* ws = rowsc + (long)bh * 2 * npad;
-            ws[qrow] = qrow < N ? lc[qt] : INFINITY;
-            ws[npad + qrow] = qrow < N ? -dl[qt] : 0.f;
+            ws[qrow] = qrow < N ? lc : INFINITY;
+            ws[npad + qrow] = qrow < N ? -dl : 0.f;
         }
     }
+    const float nlc = -lc;
+    // -delta of the lane's query in every element: the initial value of each dP accumulator, so
+    // that the MFMAs deliver dP - delta and the subtraction costs no vector-ALU instruction
+    f32x16 ndl;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) ndl[i] = -dl;
 
-    f32x16 acc[CT][QT];
-    // With one query tile per wavefront there are registers to spare for a block holding -delta of
-    // the lane's query in every element: used as the initial value of the dP accumulator, it makes
-    // the MFMAs deliver dP - delta and saves one vector-ALU instruction per score.
-    constexpr bool SEED_DELTA = QT == 1;
-    f32x16 ndl[SEED_DELTA ? QT : 1];
+    f32x16 acc[CT];
 #pragma unroll
-    for (int qt = 0; qt < QT; ++qt) {
-#pragma unroll
-        for (int ct = 0; ct < CT; ++ct) acc[ct][qt] = f32x16_zero();
-        if constexpr (SEED_DELTA) {
-#pragma unroll
-            for (int i = 0; i < 16; ++i) ndl[qt][i] = -dl[qt];
-        }
-    }
-    auto dp_seed = [&](int qt) -> f32x16 {
-        if constexpr (SEED_DELTA) return ndl[qt];
-        return f32x16_zero();
+    for (int ct = 0; ct < CT; ++ct) acc[ct] = f32x16_zero();
+
+    // The MFMAs of one unit, in issue order: each dQ update of the previous unit is followed by a
+    // pair (S, dP) of the next unit.  kind: 0 dQ, 2 S, 3 dP; arg: half*CT+ct or ks.
+    constexpr int NA = 2 * CT, NB = KS, NM = NA + 2 * NB;
+    struct Plan {
+        int kind[NM], arg[NM];
     };
-
-    Stage kst, vst;
-    if constexpr (D % 32 != 0) {
-        Stage::zero_pad(kbuf(0), tid);
-        Stage::zero_pad(kbuf(1), tid);
-    }
-    kst.load(kh, 0, tid);
-    vst.load(vh, 0, tid);
-    kst.store(kbuf(0), tid);
-    vst.store(vbuf(0), tid);
-    __syncthreads();
-
-    const int ntiles = (N + BN - 1) / BN;
-    wait_all_loads();
-    for (int t = 0; t < ntiles; ++t) {
-        const char* kc = kbuf(t & 1);
-        const char* vc = vbuf(t & 1);
-        const bool more = t + 1 < ntiles;
-        if (more) {
-            kst.load(kh, (t + 1) * BN, tid);
-            vst.load(vh, (t + 1) * BN, tid);
-        }
-        if (wave_active) {
-            const bool ragged = (t + 1) * BN > N;
-#pragma unroll
-            for (int kt = 0; kt < BN / 32; ++kt) {
-                f32x16 s[QT], dp[QT];
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    const bf16x8 ak = nat_frag(kc, STRIDE, 32 * kt + l32, ks, g);
-                    const bf16x8 av = nat_frag(vc, STRIDE, 32 * kt + l32, ks, g);
-#pragma unroll
-                    for (int qt = 0; qt < QT; ++qt) {
-                        s[qt] = mfma32(ak, qf[qt][ks], ks == 0 ? f32x16_zero() : s[qt]);
-                        dp[qt] = mfma32(av, gf[qt][ks], ks == 0 ? dp_seed(qt) : dp[qt]);
-                    }
-                }
-                bf16x8 df[QT][2];
-#pragma unroll
-                for (int qt = 0; qt < QT; ++qt) {
-                    const float nl = -lc[qt];
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const float p = fast_exp2(fmaf(s[qt][i], cs, nl));
-                        s[qt][i] = SEED_DELTA ? p * dp[qt][i] : p * (dp[qt][i] - dl[qt]);
-                    }
-                    // keys beyond N were staged as zero rows; force their dS to zero as well so
-                    // that an overflowing weight cannot turn 0 * inf into NaN
-                    if (ragged) {
-                        const int key0 = t * BN + 32 * kt + 4 * g;
-#pragma unroll
-                        for (int i = 0; i < 16; ++i)
-                            if (key0 + 8 * (i / 4) + (i % 4) >= N) s[qt][i] = 0.f;
-                    }
-                    df[qt][0] = acc_to_frag(s[qt], 0);
-                    df[qt][1] = acc_to_frag(s[qt], 1);
-                }
-                // dQ^T += K^T dS^T
-#pragma unroll
-                for (int half = 0; half < 2; ++half)
-#pragma unroll
-                    for (int ct = 0; ct < CT; ++ct) {
-                        const bf16x8 a = tr_frag(kc, STRIDE, tr_off, ct, 2 * kt + half);
-#pragma unroll
-                        for (int qt = 0; qt < QT; ++qt) acc[ct][qt] = mfma32(a, df[qt][half], acc[ct][qt]);
-                    }
+    constexpr Plan plan = [] {
+        Plan p{};
+        int n = 0, ia = 0, ib = 0;
+        while (ia < NA || ib < NB) {
+            if (ia < NA) p.kind[n] = 0, p.arg[n++] = ia++;
+            if (ib < NB) {
+                p.kind[n] = 2, p.arg[n++] = ib;
+                p.kind[n] = 3, p.arg[n++] = ib++;
             }
         }
-        if (more) {
-            kst.store(kbuf((t + 1) & 1), tid);
-            vst.store(vbuf((t + 1) & 1), tid);
-        }
-        __syncthreads();
-    }
+        return p;
+    }();
+    constexpr int LA = 3;  // LDS fragment reads run this many MFMAs ahead of their use
+    constexpr int NPW = Ring::NPW;
+    static_assert(NPW + 2 <= NM, "the tile loads must fit the MFMA slots of a unit");
+    // Slot of the first unit of an iteration after which the wavefronts synchronise.  Before it, all
+    // reads of the PREVIOUS K tile (dQ operands) must have returned, because the next loads
+    // overwrite that tile pair; after it come the first reads of the NEXT tile pair (requested LA
+    // slots ahead for the following unit), because only then is it complete.
+    static_assert(LA >= 1 && plan.kind[0] == 0 && plan.kind[1] >= 2, "the first read of the next tile is the unit's second fragment");
+    constexpr int LAST_PREV_SLOT = [] {
+        int last = 0;
+        for (int i = 0; i < NM; ++i)
+            if (plan.kind[i] == 0) last = i;
+        return last;
+    }();
+    constexpr int FIRST_NEXT_SLOT = NM - LA + 1;
+    constexpr int SYNC_SLOT = LAST_PREV_SLOT < FIRST_NEXT_SLOT ? LAST_PREV_SLOT : FIRST_NEXT_SLOT - 1;
+    constexpr bool SYNC_DRAINS = LAST_PREV_SLOT > SYNC_SLOT;  // then outstanding LDS reads are waited for
 
-    // the loop ended with a barrier: the tile buffers are free and stage the output rows
+    // Which LDS tiles a unit reads: S, dP of the NEXT unit from half hnext of (knext, vnext); the dQ
+    // update of the PREVIOUS unit from half hprev of kprev.
+    struct Where {
+        const char *knext, *vnext, *kprev;
+        int hnext, hprev;
+    };
+    auto frag = [&](const Where& w, int i) -> bf16x8 {
+        const int kd = plan.kind[i], ar = plan.arg[i];
+        if (kd == 0) return tr_frag(w.kprev, STRIDE, tr_off, ar % CT, 2 * w.hprev + ar / CT);
+        if (kd == 2) return nat_frag(w.knext, STRIDE, 32 * w.hnext + l32, ar, g);
+        return nat_frag(w.vnext, STRIDE, 32 * w.hnext + l32, ar, g);
+    };
+
+    // One unit.  cur = S, dP of the current unit (dS ends up in dp_c), nxt = accumulators of the
+    // next unit, df_p / df_c = bf16 dS fragments of the previous / current unit.  When the NEXT
+    // unit reaches past the last key (next_ragged), its score accumulator starts from the key mask
+    // instead of zero.  `pre` arrives holding the first LA fragments of this unit and leaves holding
+    // those of the unit that follows (`wn`).  side(j), j = 0 .. NPW-1, is called in slots 2, 3, ...:
+    // the tile loads.
+    auto unit = [&](auto sync, auto next_ragged, int next_key_base, const Where& w, const Where& wn, f32x16& s_c,
+                    f32x16& dp_c, f32x16& s_n, f32x16& dp_n, const u32x4 (&df_p)[2], u32x4 (&df_c)[2],
+                    bf16x8 (&pre)[LA], auto&& side) {
+        constexpr bool RAGGED = decltype(next_ragged)::value;
+        bf16x8 fr[NM];
+#pragma unroll
+        for (int i = 0; i < LA; ++i) fr[i] = pre[i];
+        if constexpr (RAGGED) s_n = key_mask_block(next_key_base, g, N);
+#pragma unroll
+        for (int i = 0; i < NM; ++i) {
+            if (i + LA < NM) fr[i + LA] = frag(w, i + LA);
+            else pre[i + LA - NM] = frag(wn, i + LA - NM);
+            const int kd = plan.kind[i], ar = plan.arg[i];
+            if (kd == 0) acc[ar % CT] = mfma32(fr[i], as_bf16x8(df_p[ar / CT]), acc[ar % CT]);
+            if (kd == 2) s_n = mfma32(fr[i], qf[ar], ar == 0 && !RAGGED ? f32x16_zero() : s_n);
+            if (kd == 3) dp_n = mfma32(fr[i], gf[ar], ar == 0 ? ndl : dp_n);
+            // vector-ALU share of this slot: elements e0..e1-1 of the current unit
+            const int e0 = i * 16 / NM, e1 = (i + 1) * 16 / NM;
+#pragma unroll
+            for (int e = e0; e < e1; ++e) {
+                const float pe = fast_exp2(fmaf(s_c[e], cs, nlc));
+                dp_c[e] = pe * dp_c[e];  // dp_c already holds dP - delta
+                if (e % 2 == 1) df_c[e / 8][(e / 2) % 4] = pack_bf16(dp_c[e - 1], dp_c[e]);
+            }
+            if (i >= 2 && i - 2 < NPW) side(i - 2);
+            if (decltype(sync)::value && i == SYNC_SLOT) Ring::template landed_barrier<SYNC_DRAINS>();
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    Ring::template landed_barrier<true>();  // pairs 0 and 1 are in LDS
+
+    f32x16 sA, dpA, sB, dpB;
+    u32x4 dfA[2], dfB[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const u32x4 z = {0u, 0u, 0u, 0u};
+        dfA[i] = z, dfB[i] = z;
+    }
+    if (wave_active) {
+        sA = key_mask_block(0, g, N);  // all zeros unless N < 32
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const bf16x8 ak = nat_frag(ring.a_tile(0), STRIDE, l32, ks, g);
+            const bf16x8 av = nat_frag(ring.b_tile(0), STRIDE, l32, ks, g);
+            sA = mfma32(ak, qf[ks], sA);
+            dpA = mfma32(av, gf[ks], ks == 0 ? ndl : dpA);
+        }
+    }
+    wait_all_loads();
+
+    // One step = one 64-key tile pair = two units.  Unit 2t: current = A; next = unit 2t+1 (second
+    // half of pair t); previous = unit 2t-1 (second half of K tile t-1; at t = 0 its dS is zero and
+    // tile 0 stands in).  Unit 2t+1: current = B; next = unit 2t+2 (first half of pair t+1; past the
+    // last tile a zero tile whose scores are never used); previous = unit 2t.  One synchronisation
+    // per step, inside unit 2t: it certifies that pair t+1 is complete (first read right after it)
+    // and that nobody reads pair t-1 any more, whose buffers the loads of pair t+3, issued during
+    // unit 2t+1, overwrite.  A pair therefore has one and a half steps to arrive.
+    auto where_a = [&](int t) { return Where{ring.a_tile(t), ring.b_tile(t), ring.a_tile(t - 1 < 0 ? 0 : t - 1), 1, 1}; };
+    auto where_b = [&](int t) { return Where{ring.a_tile(t + 1), ring.b_tile(t + 1), ring.a_tile(t), 0, 0}; };
+    bf16x8 pre[LA];
+    {
+        const Where w0 = where_a(0);
+#pragma unroll
+        for (int i = 0; i < LA; ++i) pre[i] = frag(w0, i);
+    }
+    for (int t = 0; t < ntiles; ++t) {
+        const Where wa = where_a(t), wb = where_b(t), wa1 = where_a(t + 1);
+        auto next_pair = [&](int j) { ring.fetch(t + 3, j); };
+        auto nothing = [](int) {};
+        if (wave_active) {
+            // unit 2t prepares the scores of keys 64t+32.., unit 2t+1 those of keys 64(t+1)..
+            if ((t + 1) * BN > N)
+                unit(std::true_type{}, std::true_type{}, t * BN + 32, wa, wb, sA, dpA, sB, dpB, dfB, dfA, pre, nothing);
+            else
+                unit(std::true_type{}, std::false_type{}, 0, wa, wb, sA, dpA, sB, dpB, dfB, dfA, pre, nothing);
+            if ((t + 1) * BN + 32 > N)
+                unit(std::false_type{}, std::true_type{}, (t + 1) * BN, wb, wa1, sB, dpB, sA, dpA, dfA, dfB, pre, next_pair);
+            else
+                unit(std::false_type{}, std::false_type{}, 0, wb, wa1, sB, dpB, sA, dpA, dfA, dfB, pre, next_pair);
+        } else {
+            Ring::template landed_barrier<false>();
+            ring.fetch_pair(t + 3);
+        }
+    }
+    // the last unit's contribution
+    if (wave_active) {
+#pragma unroll
+        for (int half = 0; half < 2; ++half)
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct) {
+                const bf16x8 a = tr_frag(ring.a_tile(ntiles - 1), STRIDE, tr_off, ct, 2 + half);
+                acc[ct] = mfma32(a, as_bf16x8(dfB[half]), acc[ct]);
+            }
+    }
+    wait_all_loads();  // zero tiles requested past the end must have landed before LDS is reused
+    __syncthreads();   // all tile reads are done: the buffers now stage the output rows
     if (!wave_active) return;
     char* region = smem + wave * RowStore<D>::BYTES;
-#pragma unroll
-    for (int qt = 0; qt < QT; ++qt) {
-        const int row0 = q0 + 32 * qt;
-        f32x16 tile[CT];
-#pragma unroll
-        for (int ct = 0; ct < CT; ++ct) tile[ct] = acc[ct][qt];
-        RowStore<D>::run(region, tile, scale, dq + head_off + (long)row0 * rs, rs, N - row0, lane);
-    }
+    RowStore<D>::run(region, acc, scale, dq + head_off + (long)q0 * rs, rs, N - q0, lane);
 }
 
 // ------------------------------------------------------------------------------------------ dK, dV

@@ -291,6 +291,83 @@ struct TileStage {
     }
 };
 
+// Initial value of a transposed score accumulator (lane = query, register i = key
+// key_base + 8*(i/4) + 4*g + i%4) that removes keys at or beyond N from the softmax: 0 for valid
+// keys, a huge negative number otherwise.  Those keys are zero rows in LDS, so the contraction adds
+// nothing to it, and exp2 of it is exactly 0: weight 0, dS 0, no inf * 0.
+DEVINL f32x16 key_mask_block(int key_base, int g, int N)
+{
+    f32x16 r;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) r[i] = key_base + 8 * (i / 4) + 4 * g + (i % 4) < N ? 0.f : -1.0e30f;
+    return r;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Ring of four (A tile | B tile) pairs in LDS, each tile 64 token rows of D channels in the padded
+// row layout above, filled straight from global memory by LDS-direct loads: buffers A0..A3 B0..B3.
+// A tile is a sequence of 1 KB blocks, each filled by one load of one wavefront (a block holds 64
+// consecutive 16-byte chunks of the padded rows; lanes that land on a pad chunk deposit zeros).
+// The 2*NTI blocks of a pair are dealt round robin: wavefront w issues blocks w, w+NW, ...; where
+// the list runs out a wavefront repeats the last block, so that all issue the same number NPW of
+// loads per pair -- which is what lets every wavefront wait with the same vmcnt value.
+// Tiles past the end of the sequence arrive as zero rows.
+// ---------------------------------------------------------------------------------------------
+template <int D, int NW>
+struct PairRing {
+    static constexpr int ROWS = 64;
+    static constexpr int STRIDE = tile_stride<D>();
+    static constexpr int TILE_BYTES = ROWS * STRIDE;
+    static_assert(TILE_BYTES % 1024 == 0, "a tile must be a whole number of 1 KB blocks");
+    static constexpr int NTI = TILE_BYTES / 1024, NBLK = 2 * NTI, NPW = (NBLK + NW - 1) / NW;
+    static constexpr int LDS_BYTES = 8 * TILE_BYTES;
+
+    RawBuffer a_buf, b_buf;
+    char* smem;
+    unsigned smem_addr, row_bytes;
+    unsigned voff[NPW];  // this lane's byte offset inside the tile, per load
+    int blk_lds[NPW];    // LDS offset of the block relative to buffer A0, per load
+    bool blk_is_b[NPW];
+
+    DEVINL PairRing(const bf16* a, const bf16* b, unsigned bytes, unsigned row_bytes_, char* smem_, int wave, int lane)
+        : a_buf(a, bytes), b_buf(b, bytes), smem(smem_), smem_addr(lds_address(smem_)), row_bytes(row_bytes_)
+    {
+#pragma unroll
+        for (int j = 0; j < NPW; ++j) {
+            const int blk = min(wave + NW * j, NBLK - 1);
+            blk_is_b[j] = blk >= NTI;
+            const int tb = blk_is_b[j] ? blk - NTI : blk;
+            voff[j] = padded_block_voff<D>(tb, lane, row_bytes);
+            blk_lds[j] = (blk_is_b[j] ? 4 * TILE_BYTES : 0) + tb * 1024;
+        }
+    }
+    DEVINL const char* a_tile(int ti) const { return smem + (ti & 3) * TILE_BYTES; }
+    DEVINL const char* b_tile(int ti) const { return smem + (4 + (ti & 3)) * TILE_BYTES; }
+    // load j (0 <= j < NPW) of this wavefront for pair `ti`
+    DEVINL void fetch(int ti, int j) const
+    {
+        const unsigned dst = smem_addr + (ti & 3) * TILE_BYTES + blk_lds[j];
+        load_to_lds16(blk_is_b[j] ? b_buf : a_buf, dst, voff[j] + (unsigned)ti * ROWS * row_bytes);
+    }
+    DEVINL void fetch_pair(int ti) const
+    {
+#pragma unroll
+        for (int j = 0; j < NPW; ++j) fetch(ti, j);
+    }
+    // Wait until at most one pair's worth of this wavefront's loads is still in flight, then meet
+    // the other wavefronts: after it, every pair but the most recently requested one is in LDS.
+    // DRAIN also waits for this wavefront's outstanding LDS reads.  (Plain instructions instead of
+    // __syncthreads(): its fences would wait for ALL loads.)
+    template <bool DRAIN>
+    DEVINL static void landed_barrier()
+    {
+        if constexpr (DRAIN)
+            asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(NPW) : "memory");
+        else
+            asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(NPW) : "memory");
+    }
+};
+
 // Workgroup id -> logical tile id such that tiles with consecutive logical ids run on the same XCD
 // (workgroups are dealt to the 8 XCDs round robin, and each XCD has its own L2): tiles of one
 // (batch, head) then share the K/V (or Q/dO) lines they all read.  Returns -1 for the padding ids.

@@ -38,6 +38,8 @@ struct FwdCfg {
     static constexpr int NBUF = 4;
     using Stage = TileStage<D, BN, NT>;
     static constexpr int LDS_BYTES = 2 * NBUF * Stage::BYTES;  // K0..K3 V0..V3
+    // wavefronts per SIMD the register budget is sized for: as many as LDS lets a compute unit hold
+    static constexpr int WAVES_PER_SIMD = (160 * 1024 / LDS_BYTES) * NW / 4;
 };
 
 // row sums above this (or not finite) send the workgroup to the safe pass
@@ -147,7 +149,7 @@ DEVINL void avion_fwd_safe_pass(char* smem, const SliceView& kh, const SliceView
 }
 
 template <int D, int QT, int NW>
-__global__ void __launch_bounds__(NW * 64)
+__global__ void __launch_bounds__(NW * 64, (FwdCfg<D, QT, NW>::WAVES_PER_SIMD))
 avion_fwd_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v,
                  bf16* __restrict__ o, float* __restrict__ lse, int H, int N, int nqb, int nblocks, float cs)
 {
@@ -197,51 +199,16 @@ avion_fwd_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const b
         for (int ct = 0; ct < CT; ++ct) oacc[ct][qt] = f32x16_zero();
     }
 
-    // Tile movement.  A tile buffer is a sequence of 1 KB blocks, each filled by one LDS-direct
-    // load of one wavefront (row stride STRIDE, so a block holds 64 consecutive 16-byte chunks of
-    // the padded rows; lanes that land on a pad chunk deposit zeros).  Wavefront w issues blocks
-    // w, w+NW, ... of the K tile and of the V tile; the one left-over block of each goes to
-    // wavefronts 0 and 1, and further wavefronts repeat the V one, so that every wavefront issues
-    // the same number NPW of loads per tile pair.
+    // K/V tile pairs stream through a ring of four LDS buffers each
+    using Ring = PairRing<D, NW>;
+    static_assert(Ring::TILE_BYTES == Stage::BYTES && Ring::LDS_BYTES == Cfg::LDS_BYTES, "ring and staging layouts agree");
+    constexpr int NPW = Ring::NPW;
     const int ntiles = (N + BN - 1) / BN;
-    static_assert(Stage::BYTES % 1024 == 0, "a tile must be a whole number of 1 KB blocks");
-    constexpr int NTI = Stage::BYTES / 1024, FULL = NTI / NW, REM = NTI % NW;
-    static_assert(REM == 1 && NW >= 2, "block distribution assumes one left-over block per tensor");
-    constexpr int NPW = 2 * FULL + 1;
-    const unsigned row_bytes = kh.row_bytes;
-    const RawBuffer k_buf(k + head_off, kh.bytes), v_buf(v + head_off, vh.bytes);
-    unsigned voff[FULL];
-#pragma unroll
-    for (int m = 0; m < FULL; ++m) voff[m] = padded_block_voff<D>(wave + NW * m, lane, row_bytes);
-    const unsigned left_voff = padded_block_voff<D>(NTI - 1, lane, row_bytes);
-    const RawBuffer left_buf = wave == 0 ? k_buf : v_buf;
-    const int left_lds = (wave == 0 ? 0 : 4 * Stage::BYTES) + (NTI - 1) * 1024;
-    const unsigned smem_addr = lds_address(smem);
-    // load j (0 <= j < NPW) of this wavefront for tile pair `ti`; tiles past the end arrive as zeros
-    auto fetch = [&](int ti, int j) {
-        const unsigned kb = smem_addr + (ti & 3) * Stage::BYTES, vb = kb + 4 * Stage::BYTES;
-        const unsigned base = (unsigned)ti * BN * row_bytes;
-        if (j < FULL) load_to_lds16(k_buf, kb + (wave + NW * j) * 1024, voff[j] + base);
-        else if (j < 2 * FULL) load_to_lds16(v_buf, vb + (wave + NW * (j - FULL)) * 1024, voff[j - FULL] + base);
-        else load_to_lds16(left_buf, kb + left_lds, left_voff + base);
-    };
-    auto fetch_tile = [&](int ti) {
-#pragma unroll
-        for (int j = 0; j < NPW; ++j) fetch(ti, j);
-    };
-    // Wait until at most one tile pair's worth of this wavefront's loads is still in flight, then
-    // meet the other wavefronts: after it, every tile but the most recently requested one is in
-    // LDS.  (Plain instructions instead of __syncthreads(): its fences would wait for ALL loads.)
-    auto tiles_landed_barrier = [&](auto drain_lds) {
-        if constexpr (decltype(drain_lds)::value)
-            asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(NPW) : "memory");
-        else
-            asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(NPW) : "memory");
-    };
-    fetch_tile(0);
-    fetch_tile(1);
-    fetch_tile(2);
-    tiles_landed_barrier(std::true_type{});
+    const Ring ring(k + head_off, v + head_off, kh.bytes, kh.row_bytes, smem, wave, lane);
+    ring.fetch_pair(0);
+    ring.fetch_pair(1);
+    ring.fetch_pair(2);
+    Ring::template landed_barrier<true>();
 
     // MFMAs of one unit in issue order: groups of QT sharing one LDS fragment; groups of the
     // previous unit's P V update (kind 0, arg = half*CT+ct) alternate with groups of the next
@@ -339,7 +306,7 @@ avion_fwd_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const b
                 }
                 if (qt == QT - 1) {
                     if (gi >= 2 && gi - 2 < NPW) side(gi - 2);
-                    if (decltype(sync)::value && gi == SYNC_GROUP) tiles_landed_barrier(std::bool_constant<SYNC_DRAINS>{});
+                    if (decltype(sync)::value && gi == SYNC_GROUP) Ring::template landed_barrier<SYNC_DRAINS>();
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -403,7 +370,7 @@ avion_fwd_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const b
     }
     for (int t = 0; t < ntiles; ++t) {
         const Where wa = where_a(t), wb = where_b(t), wa1 = where_a(t + 1);
-        auto next_tile = [&](int j) { fetch(t + 3, j); };
+        auto next_tile = [&](int j) { ring.fetch(t + 3, j); };
         auto nothing = [](int) {};
         if (wave_active) {
             if ((t + 1) * BN > N) {
@@ -414,8 +381,8 @@ avion_fwd_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const b
                 unit(std::false_type{}, std::false_type{}, 0, wb, wa1, sB, sA, pfA, pfB, pre, next_tile);
             }
         } else {
-            tiles_landed_barrier(std::false_type{});
-            fetch_tile(t + 3);
+            Ring::template landed_barrier<false>();
+            ring.fetch_pair(t + 3);
         }
     }
     if (wave_active) pv_only(vbuf(ntiles - 1), 1, pfB);
