@@ -79,6 +79,23 @@ int launch_fwd(const bf16* q, const bf16* k, const bf16* v, bf16* o, float* lse,
 }
 
 template <int D, int NW>
+int launch_fwd_occ(const bf16* q, const bf16* k, const bf16* v, bf16* o, float* lse, int B, int H, int N, float scale,
+                   hipStream_t st)
+{
+    using Cfg = FwdOccCfg<D, NW>;
+    static hipError_t attr = allow_lds(avion_fwd_occ_kernel<D, NW>, Cfg::LDS_BYTES);
+    if (attr != hipSuccess) return hip_fail(attr, "hipFuncSetAttribute(fwd)");
+    const int nqb = (N + Cfg::BM - 1) / Cfg::BM;
+    const long long nblocks = (long long)nqb * B * H;
+    unsigned grid;
+    if (!grid_for(nblocks, &grid)) return AVION_EUNSUPPORTED;
+    hipLaunchKernelGGL((avion_fwd_occ_kernel<D, NW>), dim3(grid), dim3(Cfg::NT), Cfg::LDS_BYTES, st, q, k, v, o, lse, H, N,
+                       nqb, (int)nblocks, scale * kLog2e);
+    const hipError_t e = hipGetLastError();
+    return e == hipSuccess ? AVION_OK : hip_fail(e, "launch avion_fwd_occ_kernel");
+}
+
+template <int D, int NW>
 int launch_dq(const bf16* q, const bf16* k, const bf16* v, const bf16* o, const bf16* dO, const float* lse, bf16* dq,
               float* rowsc, int B, int H, int N, float scale, hipStream_t st)
 {
@@ -93,6 +110,23 @@ int launch_dq(const bf16* q, const bf16* k, const bf16* v, const bf16* o, const 
                        rowsc, H, N, nqb, (int)nblocks, scale * kLog2e, scale);
     const hipError_t e = hipGetLastError();
     return e == hipSuccess ? AVION_OK : hip_fail(e, "launch avion_dq_kernel");
+}
+
+template <int D, int NW>
+int launch_dq_occ(const bf16* q, const bf16* k, const bf16* v, const bf16* o, const bf16* dO, const float* lse, bf16* dq,
+                  float* rowsc, int B, int H, int N, float scale, hipStream_t st)
+{
+    using Cfg = DqOccCfg<D, NW>;
+    static hipError_t attr = allow_lds(avion_dq_occ_kernel<D, NW>, Cfg::LDS_BYTES);
+    if (attr != hipSuccess) return hip_fail(attr, "hipFuncSetAttribute(dq)");
+    const int nqb = (N + Cfg::BM - 1) / Cfg::BM;
+    const long long nblocks = (long long)nqb * B * H;
+    unsigned grid;
+    if (!grid_for(nblocks, &grid)) return AVION_EUNSUPPORTED;
+    hipLaunchKernelGGL((avion_dq_occ_kernel<D, NW>), dim3(grid), dim3(Cfg::NT), Cfg::LDS_BYTES, st, q, k, v, o, dO, lse,
+                       dq, rowsc, H, N, nqb, (int)nblocks, scale * kLog2e, scale);
+    const hipError_t e = hipGetLastError();
+    return e == hipSuccess ? AVION_OK : hip_fail(e, "launch avion_dq_occ_kernel");
 }
 
 template <int D, int NW>
@@ -121,6 +155,7 @@ int fwd_dispatch(const bf16* q, const bf16* k, const bf16* v, bf16* o, float* ls
     if constexpr (D == 64) {
         static const int vf = variant("FWD", 0);
         if (vf == 6) return launch_fwd<D, 1, 6>(q, k, v, o, lse, B, H, N, scale, st);
+        if (vf == 10) return launch_fwd_occ<D, 4>(q, k, v, o, lse, B, H, N, scale, st);
     }
     return launch_fwd<D, 1, 4>(q, k, v, o, lse, B, H, N, scale, st);
 }
@@ -129,6 +164,10 @@ template <int D>
 int dq_dispatch(const bf16* q, const bf16* k, const bf16* v, const bf16* o, const float* lse, const bf16* dO, bf16* dq,
                 float* rowsc, int B, int H, int N, float scale, hipStream_t st)
 {
+    if constexpr (D == 64) {
+        static const int vq = variant("DQ", 0);
+        if (vq == 10) return launch_dq_occ<D, 4>(q, k, v, o, dO, lse, dq, rowsc, B, H, N, scale, st);
+    }
     return launch_dq<D, 4>(q, k, v, o, dO, lse, dq, rowsc, B, H, N, scale, st);
 }
 

@@ -266,6 +266,134 @@ avion_dq_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf
     RowStore<D>::run(region, acc, scale, dq + head_off + (long)q0 * rs, rs, N - q0, lane);
 }
 
+// Occupancy-oriented dQ kernel.  Same mathematics and layouts as avion_dq_kernel, but no software
+// pipelining: each wavefront runs S^T / dP^T, the vector work and the dQ^T update of one 32-key unit
+// after the other with few live registers, and a compute unit holds many wavefronts (two K/V tile
+// pairs in LDS), so that while one wavefront waits for its matrix instructions another one issues
+// vector work.  One workgroup barrier per 64-key tile pair: passing it certifies that the next pair
+// has landed and that the previous one is no longer read, so its buffers can be refilled.
+template <int D, int NW>
+struct DqOccCfg {
+    static constexpr int BN = 64;
+    static constexpr int NT = NW * 64;
+    static constexpr int BM = 32 * NW;
+    using Ring = PairRing<D, NW, 2>;
+    static constexpr int LDS_BYTES = Ring::LDS_BYTES;
+    static constexpr int WAVES_PER_SIMD = D == 64 ? 3 : 2;
+};
+
+template <int D, int NW>
+__global__ void __launch_bounds__(NW * 64, (DqOccCfg<D, NW>::WAVES_PER_SIMD))
+avion_dq_occ_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v,
+                    const bf16* __restrict__ o, const bf16* __restrict__ dO, const float* __restrict__ lse,
+                    bf16* __restrict__ dq, float* __restrict__ rowsc, int H, int N, int nqb, int nblocks,
+                    float cs, float scale)
+{
+    using Cfg = DqOccCfg<D, NW>;
+    using Ring = typename Cfg::Ring;
+    constexpr int BN = Cfg::BN, BM = Cfg::BM, STRIDE = Ring::STRIDE;
+    constexpr int KS = D / 16, CT = (D + 31) / 32;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+
+    const int logical = xcd_local_id(blockIdx.x, nblocks);
+    if (logical < 0) return;
+    const int bh = logical / nqb, qb = logical % nqb;
+    const int b = bh / H, h = bh % H;
+    const int tid = threadIdx.x, lane = tid % 64, l32 = lane % 32, g = lane / 32;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
+    const long rs = (long)H * D;
+    const long head_off = ((long)b * N * H + h) * D;
+    const SliceView kh(k + head_off, rs, N, D);
+    const int q0 = qb * BM + wave * 32;
+    const bool wave_active = q0 < N;
+    const int tr_off = tr_lane_offset(lane, STRIDE);
+    const int ntiles = (N + BN - 1) / BN;
+
+    const Ring ring(k + head_off, v + head_off, kh.bytes, kh.row_bytes, smem, wave, lane);
+    ring.fetch_pair(0);
+
+    // Q and dO fragments (B operands), delta and LSE per lane
+    bf16x8 qf[KS], gf[KS];
+    float lc, dl;
+    {
+        const int row = min(q0 + l32, N - 1);
+        const long off = head_off + (long)row * rs + g * 8;
+        float part = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            qf[ks] = *reinterpret_cast<const bf16x8*>(q + off + ks * 16);
+            gf[ks] = *reinterpret_cast<const bf16x8*>(dO + off + ks * 16);
+            const bf16x8 of = *reinterpret_cast<const bf16x8*>(o + off + ks * 16);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) part = fmaf((float)of[e], (float)gf[ks][e], part);
+        }
+        dl = both_halves_sum(part);
+        lc = lse[(long)bh * N + row] * kLog2e;
+        // per-query scalars for the dK/dV pass, in the form it consumes them: LSE*log2e and -delta,
+        // each array padded to a multiple of 64 rows with +inf (weight 0) and 0
+        const int qrow = q0 + l32, npad = (N + 63) & ~63;
+        if (g == 0 && qrow < npad) {
+            float* ws = rowsc + (long)bh * 2 * npad;
+            ws[qrow] = qrow < N ? lc : INFINITY;
+            ws[npad + qrow] = qrow < N ? -dl : 0.f;
+        }
+    }
+    const float nlc = -lc;
+    f32x16 acc[CT];
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) acc[ct] = f32x16_zero();
+
+    wait_all_loads();
+    Ring::template landed_barrier<false, 0>();  // tile pair 0 is in LDS
+
+    // one 32-key unit: rows 32*hk.. of the tile pair; RAGGED units reach past the last key and
+    // start the score accumulator from the key mask instead of zero
+    auto unit = [&](auto ragged, const char* kt, const char* vt, int hk, int key_base) {
+        constexpr bool RAGGED = decltype(ragged)::value;
+        f32x16 s, dp;
+        if constexpr (RAGGED) s = key_mask_block(key_base, g, N);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const bf16x8 ak = nat_frag(kt, STRIDE, 32 * hk + l32, ks, g);
+            const bf16x8 av = nat_frag(vt, STRIDE, 32 * hk + l32, ks, g);
+            s = mfma32(ak, qf[ks], ks == 0 && !RAGGED ? f32x16_zero() : s);
+            dp = mfma32(av, gf[ks], ks == 0 ? f32x16_zero() : dp);
+        }
+        // the K^T operands are requested before the vector work so that they are there after it
+        bf16x8 kt_f[2][CT];
+#pragma unroll
+        for (int half = 0; half < 2; ++half)
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct) kt_f[half][ct] = tr_frag(kt, STRIDE, tr_off, ct, 2 * hk + half);
+        u32x4 df[2];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const float pe = fast_exp2(fmaf(s[i], cs, nlc));
+            s[i] = pe * (dp[i] - dl);
+            if (i % 2 == 1) df[i / 8][(i / 2) % 4] = pack_bf16(s[i - 1], s[i]);
+        }
+#pragma unroll
+        for (int half = 0; half < 2; ++half)
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct) acc[ct] = mfma32(kt_f[half][ct], as_bf16x8(df[half]), acc[ct]);
+    };
+
+    for (int t = 0; t < ntiles; ++t) {
+        ring.fetch_pair(t + 1);  // into the buffers of pair t-1, which nobody reads any more
+        if (wave_active) {
+#pragma unroll
+            for (int hk = 0; hk < 2; ++hk) {
+                const int key_base = t * BN + 32 * hk;
+                if (key_base + 32 > N) unit(std::true_type{}, ring.a_tile(t), ring.b_tile(t), hk, key_base);
+                else unit(std::false_type{}, ring.a_tile(t), ring.b_tile(t), hk, key_base);
+            }
+        }
+        Ring::template landed_barrier<false, 0>();  // pair t+1 has landed; pair t is no longer read
+    }
+    if (!wave_active) return;
+    RowStore<D>::run(smem + wave * RowStore<D>::BYTES, acc, scale, dq + head_off + (long)q0 * rs, rs, N - q0, lane);
+}
+
 // ------------------------------------------------------------------------------------------ dK, dV
 // One wavefront owns 32 keys; the workgroup's NW wavefronts share LDS tiles of BQ = 64 queries
 // (Q and dO rows, LSE*log2e and -delta), four buffers deep, filled straight from global memory by

@@ -304,8 +304,8 @@ DEVINL f32x16 key_mask_block(int key_base, int g, int N)
 }
 
 // ---------------------------------------------------------------------------------------------
-// Ring of four (A tile | B tile) pairs in LDS, each tile 64 token rows of D channels in the padded
-// row layout above, filled straight from global memory by LDS-direct loads: buffers A0..A3 B0..B3.
+// Ring of NBUF (A tile | B tile) pairs in LDS, each tile 64 token rows of D channels in the padded
+// row layout above, filled straight from global memory by LDS-direct loads: buffers A0.. then B0..
 // A tile is a sequence of 1 KB blocks, each filled by one load of one wavefront (a block holds 64
 // consecutive 16-byte chunks of the padded rows; lanes that land on a pad chunk deposit zeros).
 // The 2*NTI blocks of a pair are dealt round robin: wavefront w issues blocks w, w+NW, ...; where
@@ -313,14 +313,15 @@ DEVINL f32x16 key_mask_block(int key_base, int g, int N)
 // loads per pair -- which is what lets every wavefront wait with the same vmcnt value.
 // Tiles past the end of the sequence arrive as zero rows.
 // ---------------------------------------------------------------------------------------------
-template <int D, int NW>
+template <int D, int NW, int NBUF = 4>
 struct PairRing {
     static constexpr int ROWS = 64;
     static constexpr int STRIDE = tile_stride<D>();
     static constexpr int TILE_BYTES = ROWS * STRIDE;
     static_assert(TILE_BYTES % 1024 == 0, "a tile must be a whole number of 1 KB blocks");
     static constexpr int NTI = TILE_BYTES / 1024, NBLK = 2 * NTI, NPW = (NBLK + NW - 1) / NW;
-    static constexpr int LDS_BYTES = 8 * TILE_BYTES;
+    static_assert((NBUF & (NBUF - 1)) == 0, "ring size must be a power of two");
+    static constexpr int LDS_BYTES = 2 * NBUF * TILE_BYTES;
 
     RawBuffer a_buf, b_buf;
     char* smem;
@@ -338,15 +339,15 @@ struct PairRing {
             blk_is_b[j] = blk >= NTI;
             const int tb = blk_is_b[j] ? blk - NTI : blk;
             voff[j] = padded_block_voff<D>(tb, lane, row_bytes);
-            blk_lds[j] = (blk_is_b[j] ? 4 * TILE_BYTES : 0) + tb * 1024;
+            blk_lds[j] = (blk_is_b[j] ? NBUF * TILE_BYTES : 0) + tb * 1024;
         }
     }
-    DEVINL const char* a_tile(int ti) const { return smem + (ti & 3) * TILE_BYTES; }
-    DEVINL const char* b_tile(int ti) const { return smem + (4 + (ti & 3)) * TILE_BYTES; }
+    DEVINL const char* a_tile(int ti) const { return smem + (ti & (NBUF - 1)) * TILE_BYTES; }
+    DEVINL const char* b_tile(int ti) const { return smem + (NBUF + (ti & (NBUF - 1))) * TILE_BYTES; }
     // load j (0 <= j < NPW) of this wavefront for pair `ti`
     DEVINL void fetch(int ti, int j) const
     {
-        const unsigned dst = smem_addr + (ti & 3) * TILE_BYTES + blk_lds[j];
+        const unsigned dst = smem_addr + (ti & (NBUF - 1)) * TILE_BYTES + blk_lds[j];
         load_to_lds16(blk_is_b[j] ? b_buf : a_buf, dst, voff[j] + (unsigned)ti * ROWS * row_bytes);
     }
     DEVINL void fetch_pair(int ti) const
@@ -354,17 +355,17 @@ struct PairRing {
 #pragma unroll
         for (int j = 0; j < NPW; ++j) fetch(ti, j);
     }
-    // Wait until at most one pair's worth of this wavefront's loads is still in flight, then meet
-    // the other wavefronts: after it, every pair but the most recently requested one is in LDS.
-    // DRAIN also waits for this wavefront's outstanding LDS reads.  (Plain instructions instead of
-    // __syncthreads(): its fences would wait for ALL loads.)
-    template <bool DRAIN>
+    // Wait until at most IN_FLIGHT pairs' worth of this wavefront's loads is still outstanding, then
+    // meet the other wavefronts: after it, every pair but the IN_FLIGHT most recently requested ones
+    // is in LDS.  DRAIN also waits for this wavefront's outstanding LDS reads.  (Plain instructions
+    // instead of __syncthreads(): its fences would wait for ALL loads.)
+    template <bool DRAIN, int IN_FLIGHT = 1>
     DEVINL static void landed_barrier()
     {
         if constexpr (DRAIN)
-            asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(NPW) : "memory");
+            asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(IN_FLIGHT * NPW) : "memory");
         else
-            asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(NPW) : "memory");
+            asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(IN_FLIGHT * NPW) : "memory");
     }
 };
 

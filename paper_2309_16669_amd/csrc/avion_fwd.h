@@ -51,12 +51,12 @@ template <int D, int QT, int NW>
 DEVINL void avion_fwd_safe_pass(char* smem, const SliceView& kh, const SliceView& vh, const bf16x8 (&qf)[QT][D / 16],
                                 f32x16 (&oacc)[(D + 31) / 32][QT], float (&m_used)[QT], float (&lsum)[QT],
                                 float (&rsum)[QT], int N, float cs, bool wave_active, int tid, int l32, int g,
-                                int tr_off)
+                                int tr_off, int v_off)
 {
     using Stage = typename FwdCfg<D, QT, NW>::Stage;
     constexpr int BN = 64, STRIDE = Stage::STRIDE, KS = D / 16, CT = (D + 31) / 32;
     auto kbuf = [&](int i) { return smem + i * Stage::BYTES; };
-    auto vbuf = [&](int i) { return smem + (4 + i) * Stage::BYTES; };
+    auto vbuf = [&](int i) { return smem + v_off + i * Stage::BYTES; };  // two K and two V buffers are used
 #pragma unroll
     for (int qt = 0; qt < QT; ++qt) {
         m_used[qt] = -INFINITY;
@@ -398,7 +398,8 @@ avion_fwd_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const b
     }
     wait_all_loads();  // zero tiles requested past the end must have landed before LDS is reused
     if (__syncthreads_or(bad ? 1 : 0))
-        avion_fwd_safe_pass<D, QT, NW>(smem, kh, vh, qf, oacc, m_used, lsum, rsum, N, cs, wave_active, tid, l32, g, tr_off);
+        avion_fwd_safe_pass<D, QT, NW>(smem, kh, vh, qf, oacc, m_used, lsum, rsum, N, cs, wave_active, tid, l32, g, tr_off,
+                                       4 * Stage::BYTES);
 
     // every wavefront is past its last tile read (barrier above): the tile buffers are free and
     // serve as the per-wavefront staging area of the output rows
@@ -420,4 +421,137 @@ avion_fwd_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const b
         RowStore<D>::run(region, tile, 1.0f, oh + (long)row0 * rs, rs, N - row0, lane);
         if (g == 0 && row0 + l32 < N) lse[(long)bh * N + row0 + l32] = (m_used[qt] + __builtin_amdgcn_logf(l)) * kLn2;
     }
+}
+
+
+// ---------------------------------------------------------------------------------------------
+// Occupancy-oriented forward kernel.  Same mathematics, layouts and fallback as avion_fwd_kernel,
+// but no software pipelining: each wavefront runs S^T, softmax, P V of one 32-key unit after the
+// other with few live registers, and a compute unit holds many wavefronts (small LDS footprint:
+// two K/V tile pairs), so that while one wavefront waits for its matrix instructions another one
+// issues vector work.  One workgroup barrier per 64-key tile: passing it certifies that the next
+// tile pair has landed and that the previous one is no longer read, so its buffers can be refilled.
+// ---------------------------------------------------------------------------------------------
+template <int D, int NW>
+struct FwdOccCfg {
+    static constexpr int BN = 64;
+    static constexpr int NT = NW * 64;
+    static constexpr int BM = 32 * NW;
+    using Ring = PairRing<D, NW, 2>;
+    static constexpr int LDS_BYTES = Ring::LDS_BYTES;
+    static constexpr int WAVES_PER_SIMD = (160 * 1024 / LDS_BYTES) * NW / 4 > 4 ? 4 : (160 * 1024 / LDS_BYTES) * NW / 4;
+};
+
+template <int D, int NW>
+__global__ void __launch_bounds__(NW * 64, (FwdOccCfg<D, NW>::WAVES_PER_SIMD))
+avion_fwd_occ_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v,
+                     bf16* __restrict__ o, float* __restrict__ lse, int H, int N, int nqb, int nblocks, float cs)
+{
+    using Cfg = FwdOccCfg<D, NW>;
+    using Ring = typename Cfg::Ring;
+    constexpr int BN = Cfg::BN, BM = Cfg::BM, STRIDE = Ring::STRIDE;
+    constexpr int KS = D / 16, CT = (D + 31) / 32;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+
+    const int logical = xcd_local_id(blockIdx.x, nblocks);
+    if (logical < 0) return;
+    const int bh = logical / nqb, qb = logical % nqb;
+    const int b = bh / H, h = bh % H;
+    const int tid = threadIdx.x, lane = tid % 64, l32 = lane % 32, g = lane / 32;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
+    const long rs = (long)H * D;
+    const long head_off = ((long)b * N * H + h) * D;
+    const SliceView kh(k + head_off, rs, N, D);
+    const SliceView vh(v + head_off, rs, N, D);
+    const int q0 = qb * BM + wave * 32;
+    const bool wave_active = q0 < N;
+    const int tr_off = tr_lane_offset(lane, STRIDE);
+    const int ntiles = (N + BN - 1) / BN;
+
+    const Ring ring(k + head_off, v + head_off, kh.bytes, kh.row_bytes, smem, wave, lane);
+    ring.fetch_pair(0);
+
+    bf16x8 qf[1][KS];
+    {
+        const int row = min(q0 + l32, N - 1);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+            qf[0][ks] = *reinterpret_cast<const bf16x8*>(q + head_off + (long)row * rs + ks * 16 + g * 8);
+    }
+    f32x16 oacc[CT][1];
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) oacc[ct][0] = f32x16_zero();
+    float m_used[1] = {0.f}, lsum[1] = {0.f}, rsum[1] = {0.f};
+
+    wait_all_loads();
+    Ring::template landed_barrier<false, 0>();  // tile pair 0 is in LDS
+
+    // S^T of one unit (32 keys starting at row 32*hk of the K tile); RAGGED units reach past the
+    // last key and start from the key mask instead of zero
+    auto scores = [&](auto ragged, const char* kt, int hk, int key_base) -> f32x16 {
+        constexpr bool RAGGED = decltype(ragged)::value;
+        f32x16 s;
+        if constexpr (RAGGED) s = key_mask_block(key_base, g, N);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+            s = mfma32(nat_frag(kt, STRIDE, 32 * hk + l32, ks, g), qf[0][ks], ks == 0 && !RAGGED ? f32x16_zero() : s);
+        return s;
+    };
+    // reference maximum: over the first 32 keys
+    if (wave_active) m_used[0] = both_halves_max(max16(scores(std::true_type{}, ring.a_tile(0), 0, 0))) * cs;
+
+    const bf16x2 ones = {(bf16)1.0f, (bf16)1.0f};
+    for (int t = 0; t < ntiles; ++t) {
+        ring.fetch_pair(t + 1);  // into the buffers of pair t-1, which nobody reads any more
+        if (wave_active) {
+            const char* kt = ring.a_tile(t);
+            const char* vt = ring.b_tile(t);
+#pragma unroll
+            for (int hk = 0; hk < 2; ++hk) {
+                const int key_base = t * BN + 32 * hk;
+                f32x16 s;
+                if (key_base + 32 > N) s = scores(std::true_type{}, kt, hk, key_base);
+                else s = scores(std::false_type{}, kt, hk, key_base);
+                // the V^T operands are requested before the vector work so that they are there after it
+                bf16x8 vf[2][CT];
+#pragma unroll
+                for (int half = 0; half < 2; ++half)
+#pragma unroll
+                    for (int ct = 0; ct < CT; ++ct) vf[half][ct] = tr_frag(vt, STRIDE, tr_off, ct, 2 * hk + half);
+                u32x4 pf[2];
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const float p = fast_exp2(fmaf(s[i], cs, -m_used[0]));
+                    s[i] = p;
+                    lsum[0] += p;
+                    if (i % 2 == 1) {
+                        const unsigned wgt = pack_bf16(s[i - 1], p);
+                        pf[i / 8][(i / 2) % 4] = wgt;
+                        rsum[0] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, wgt), ones, rsum[0], false);
+                    }
+                }
+#pragma unroll
+                for (int half = 0; half < 2; ++half)
+#pragma unroll
+                    for (int ct = 0; ct < CT; ++ct) oacc[ct][0] = mfma32(vf[half][ct], as_bf16x8(pf[half]), oacc[ct][0]);
+            }
+        }
+        Ring::template landed_barrier<false, 0>();  // pair t+1 has landed; pair t is no longer read
+    }
+
+    bool bad = false;
+    if (wave_active) bad = !(both_halves_sum(lsum[0]) <= kRowSumLimit);
+    if (__syncthreads_or(bad ? 1 : 0))
+        avion_fwd_safe_pass<D, 1, NW>(smem, kh, vh, qf, oacc, m_used, lsum, rsum, N, cs, wave_active, tid, l32, g, tr_off,
+                                      2 * Ring::TILE_BYTES);
+    if (!wave_active) return;
+    const float l = both_halves_sum(lsum[0]);
+    const float inv = 1.0f / both_halves_sum(rsum[0]);
+    f32x16 tile[CT];
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) tile[ct][i] = oacc[ct][0][i] * inv;
+    RowStore<D>::run(smem + wave * RowStore<D>::BYTES, tile, 1.0f, o + head_off + (long)q0 * rs, rs, N - q0, lane);
+    if (g == 0 && q0 + l32 < N) lse[(long)bh * N + q0 + l32] = (m_used[0] + __builtin_amdgcn_logf(l)) * kLn2;
 }
