@@ -146,17 +146,31 @@ int launch_dkdv(const bf16* q, const bf16* k, const bf16* v, const bf16* dO, con
     return e == hipSuccess ? AVION_OK : hip_fail(e, "launch avion_dkdv_kernel");
 }
 
+template <int D, int NW>
+int launch_dkdv_occ(const bf16* q, const bf16* k, const bf16* v, const bf16* dO, const float* rowsc, bf16* dk, bf16* dv,
+                    int B, int H, int N, float scale, hipStream_t st)
+{
+    using Cfg = DkvOccCfg<D, NW>;
+    static hipError_t attr = allow_lds(avion_dkdv_occ_kernel<D, NW>, Cfg::LDS_BYTES);
+    if (attr != hipSuccess) return hip_fail(attr, "hipFuncSetAttribute(dkdv)");
+    const int nkb = (N + Cfg::BNK - 1) / Cfg::BNK;
+    const long long nblocks = (long long)nkb * B * H;
+    unsigned grid;
+    if (!grid_for(nblocks, &grid)) return AVION_EUNSUPPORTED;
+    hipLaunchKernelGGL((avion_dkdv_occ_kernel<D, NW>), dim3(grid), dim3(Cfg::NT), Cfg::LDS_BYTES, st, q, k, v, dO, rowsc,
+                       dk, dv, H, N, nkb, (int)nblocks, scale * kLog2e, scale);
+    const hipError_t e = hipGetLastError();
+    return e == hipSuccess ? AVION_OK : hip_fail(e, "launch avion_dkdv_occ_kernel");
+}
+
 // Kernel instances.  Only instances that keep every array in registers (no scratch, no spills) are
 // dispatched; AVION_VARIANT_FWD / AVION_VARIANT_DKDV select the alternatives kept for tuning sweeps.
 template <int D>
 int fwd_dispatch(const bf16* q, const bf16* k, const bf16* v, bf16* o, float* lse, int B, int H, int N, float scale,
                  hipStream_t st)
 {
-    if constexpr (D == 64) {
-        static const int vf = variant("FWD", 0);
-        if (vf == 6) return launch_fwd<D, 1, 6>(q, k, v, o, lse, B, H, N, scale, st);
-        if (vf == 10) return launch_fwd_occ<D, 4>(q, k, v, o, lse, B, H, N, scale, st);
-    }
+    static const int vf = variant("FWD", 0);
+    if (vf == 10) return launch_fwd_occ<D, 4>(q, k, v, o, lse, B, H, N, scale, st);
     return launch_fwd<D, 1, 4>(q, k, v, o, lse, B, H, N, scale, st);
 }
 
@@ -164,10 +178,8 @@ template <int D>
 int dq_dispatch(const bf16* q, const bf16* k, const bf16* v, const bf16* o, const float* lse, const bf16* dO, bf16* dq,
                 float* rowsc, int B, int H, int N, float scale, hipStream_t st)
 {
-    if constexpr (D == 64) {
-        static const int vq = variant("DQ", 0);
-        if (vq == 10) return launch_dq_occ<D, 4>(q, k, v, o, dO, lse, dq, rowsc, B, H, N, scale, st);
-    }
+    static const int vq = variant("DQ", 0);
+    if (vq == 10) return launch_dq_occ<D, 4>(q, k, v, o, dO, lse, dq, rowsc, B, H, N, scale, st);
     return launch_dq<D, 4>(q, k, v, o, dO, lse, dq, rowsc, B, H, N, scale, st);
 }
 
@@ -175,10 +187,8 @@ template <int D>
 int dkdv_dispatch(const bf16* q, const bf16* k, const bf16* v, const bf16* dO, bf16* dk, bf16* dv, const float* rowsc,
                   int B, int H, int N, float scale, hipStream_t st)
 {
-    if constexpr (D == 64) {
-        static const int vk = variant("DKDV", 0);
-        if (vk == 2) return launch_dkdv<D, 8>(q, k, v, dO, rowsc, dk, dv, B, H, N, scale, st);
-    }
+    static const int vk = variant("DKDV", 0);
+    if (vk == 10) return launch_dkdv_occ<D, 4>(q, k, v, dO, rowsc, dk, dv, B, H, N, scale, st);
     return launch_dkdv<D, 4>(q, k, v, dO, rowsc, dk, dv, B, H, N, scale, st);
 }
 

@@ -279,7 +279,7 @@ struct DqOccCfg {
     static constexpr int BM = 32 * NW;
     using Ring = PairRing<D, NW, 2>;
     static constexpr int LDS_BYTES = Ring::LDS_BYTES;
-    static constexpr int WAVES_PER_SIMD = D == 64 ? 3 : 2;
+    static constexpr int WAVES_PER_SIMD = D == 64 ? 3 : 2;  // LDS would allow more; registers do not
 };
 
 template <int D, int NW>
@@ -493,7 +493,7 @@ avion_dkdv_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const 
                                : lane < 32  ? (unsigned)(npad * 4 + (lane - 16) * 16)
                                             : kOutOfRangeBase;
     const unsigned left_step = left_is_rows ? BQ * row_bytes : BQ * 4;  // per tile
-    const RawBuffer left_buf = wave == 0 ? q_buf : wave == 1 ? g_buf : rowsc_buf;
+    const RawBuffer left_buf = pick(wave == 0, q_buf, pick(wave == 1, g_buf, rowsc_buf));
     const int left_lds = wave == 0 ? (NTI - 1) * 1024 : wave == 1 ? OFF_G + (NTI - 1) * 1024 : OFF_ROW;
     const unsigned smem_addr = lds_address(smem);
     const int ntiles = (N + BQ - 1) / BQ;
@@ -706,6 +706,135 @@ avion_dkdv_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const 
     if (wave_active) accumulate(tilebuf(ntiles - 1), 1, pfB, dfB);  // the last unit's contribution
     wait_all_loads();  // zero tiles requested past the end must have landed before LDS is reused
     __syncthreads();   // all tile reads are done: the buffers now stage the output rows
+    if (!wave_active) return;
+    char* region = smem + wave * RowStore<D>::BYTES;
+    RowStore<D>::run(region, dka, scale, dk + head_off + (long)k0 * rs, rs, N - k0, lane);
+    RowStore<D>::run(region, dva, 1.0f, dv + head_off + (long)k0 * rs, rs, N - k0, lane);
+}
+
+// Occupancy-oriented dK/dV kernel.  Same mathematics and layouts as avion_dkdv_kernel, but no
+// software pipelining: each wavefront runs S / dP, the vector work and the dV^T / dK^T updates of
+// one 32-query unit after the other, with two (Q | dO | scalars) buffers in LDS, so that more
+// wavefronts fit a compute unit and cover each other's waits.  One workgroup barrier per 64-query
+// tile: passing it certifies that the next tile has landed and that the previous one is no longer
+// read, so its buffer can be refilled.
+template <int D, int NW>
+struct DkvOccCfg {
+    static constexpr int BQ = 64;
+    static constexpr int NT = NW * 64;
+    static constexpr int BNK = 32 * NW;
+    using Ring = RowsAndScalarsRing<D, NW, 2>;
+    static constexpr int LDS_BYTES = Ring::LDS_BYTES;
+    static constexpr int WAVES_PER_SIMD = 2;  // a floor for the register budget; D = 64 fits three
+};
+
+template <int D, int NW>
+__global__ void __launch_bounds__(NW * 64, (DkvOccCfg<D, NW>::WAVES_PER_SIMD))
+avion_dkdv_occ_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v,
+                      const bf16* __restrict__ dO, const float* __restrict__ rowsc, bf16* __restrict__ dk,
+                      bf16* __restrict__ dv, int H, int N, int nkb, int nblocks, float cs, float scale)
+{
+    using Cfg = DkvOccCfg<D, NW>;
+    using Ring = typename Cfg::Ring;
+    constexpr int BQ = Cfg::BQ, BNK = Cfg::BNK, STRIDE = Ring::STRIDE;
+    constexpr int KS = D / 16, CT = (D + 31) / 32;
+    constexpr int OFF_G = Ring::OFF_B, OFF_ROW = Ring::OFF_SCALARS;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+
+    const int logical = xcd_local_id(blockIdx.x, nblocks);
+    if (logical < 0) return;
+    const int bh = logical / nkb, kb = logical % nkb;
+    const int b = bh / H, h = bh % H;
+    const int tid = threadIdx.x, lane = tid % 64, l32 = lane % 32, g = lane / 32;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
+    const long rs = (long)H * D;
+    const long head_off = ((long)b * N * H + h) * D;
+    const SliceView qh(q + head_off, rs, N, D);
+    const int npad = (N + 63) & ~63;
+    const int ntiles = (N + BQ - 1) / BQ;
+    const int k0 = kb * BNK + wave * 32;  // first key of this wavefront
+    const bool wave_active = k0 < N;
+    const int tr_off = tr_lane_offset(lane, STRIDE);
+
+    const Ring ring(q + head_off, dO + head_off, qh.bytes, qh.row_bytes, rowsc + (long)bh * 2 * npad, npad, ntiles, smem,
+                    wave, lane);
+    ring.fetch_tile(0);
+
+    // K and V fragments (B operands: lane = key) stay in registers
+    bf16x8 kf[KS], vf[KS];
+    {
+        const int row = min(k0 + l32, N - 1);
+        const long off = head_off + (long)row * rs + g * 8;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            kf[ks] = *reinterpret_cast<const bf16x8*>(k + off + ks * 16);
+            vf[ks] = *reinterpret_cast<const bf16x8*>(v + off + ks * 16);
+        }
+    }
+    f32x16 dka[CT], dva[CT];
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) {
+        dka[ct] = f32x16_zero();
+        dva[ct] = f32x16_zero();
+    }
+    wait_all_loads();
+    Ring::template landed_barrier<false, 0>();  // tile 0 is in LDS
+
+    for (int t = 0; t < ntiles; ++t) {
+        ring.fetch_tile(t + 1);  // into the buffer of tile t-1, which nobody reads any more
+        if (wave_active) {
+            const char* buf = ring.buf(t);
+#pragma unroll
+            for (int hq = 0; hq < 2; ++hq) {
+                const float* rowv = reinterpret_cast<const float*>(buf + OFF_ROW) + 32 * hq + 4 * g;
+                // dP starts from -delta of the accumulator rows' queries (broadcast LDS reads)
+                f32x16 s, dp;
+#pragma unroll
+                for (int a4 = 0; a4 < 4; ++a4) {
+                    const f32x4 d4 = *reinterpret_cast<const f32x4*>(rowv + BQ + 8 * a4);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) dp[4 * a4 + e] = d4[e];
+                }
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    const bf16x8 aq = nat_frag(buf, STRIDE, 32 * hq + l32, ks, g);
+                    const bf16x8 ag = nat_frag(buf + OFF_G, STRIDE, 32 * hq + l32, ks, g);
+                    s = mfma32(aq, kf[ks], ks == 0 ? f32x16_zero() : s);
+                    dp = mfma32(ag, vf[ks], dp);
+                }
+                f32x4 l4[4];
+#pragma unroll
+                for (int a4 = 0; a4 < 4; ++a4) l4[a4] = *reinterpret_cast<const f32x4*>(rowv + 8 * a4);
+                // per query half (16 queries): transposed operands requested before the vector work
+#pragma unroll
+                for (int half = 0; half < 2; ++half) {
+                    bf16x8 tg[CT], tq[CT];
+#pragma unroll
+                    for (int ct = 0; ct < CT; ++ct) {
+                        tg[ct] = tr_frag(buf + OFF_G, STRIDE, tr_off, ct, 2 * hq + half);
+                        tq[ct] = tr_frag(buf, STRIDE, tr_off, ct, 2 * hq + half);
+                    }
+                    u32x4 pf, df;
+#pragma unroll
+                    for (int e = 8 * half; e < 8 * half + 8; ++e) {
+                        const float pe = fast_exp2(fmaf(s[e], cs, -l4[e / 4][e % 4]));
+                        s[e] = pe;
+                        dp[e] = pe * dp[e];
+                        if (e % 2 == 1) {
+                            pf[(e / 2) % 4] = pack_bf16(s[e - 1], s[e]);
+                            df[(e / 2) % 4] = pack_bf16(dp[e - 1], dp[e]);
+                        }
+                    }
+#pragma unroll
+                    for (int ct = 0; ct < CT; ++ct) {
+                        dva[ct] = mfma32(tg[ct], as_bf16x8(pf), dva[ct]);
+                        dka[ct] = mfma32(tq[ct], as_bf16x8(df), dka[ct]);
+                    }
+                }
+            }
+        }
+        Ring::template landed_barrier<false, 0>();  // tile t+1 has landed; tile t is no longer read
+    }
     if (!wave_active) return;
     char* region = smem + wave * RowStore<D>::BYTES;
     RowStore<D>::run(region, dka, scale, dk + head_off + (long)k0 * rs, rs, N - k0, lane);

@@ -190,6 +190,15 @@ struct RawBuffer {
     }
 };
 DEVINL unsigned lds_address(const char* p) { return (unsigned)(unsigned long)(const lds_char*)p; }
+// one of two / three descriptors, chosen by a wavefront-uniform condition; the result is moved to
+// scalar registers explicitly because the compiler may have kept the selection in vector registers
+DEVINL RawBuffer pick(bool first, const RawBuffer& a, const RawBuffer& b)
+{
+    RawBuffer r = first ? a : b;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) r.words[i] = __builtin_amdgcn_readfirstlane(r.words[i]);
+    return r;
+}
 DEVINL void load_to_lds16(const RawBuffer& buf, unsigned lds_addr, unsigned voff)
 {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
@@ -328,7 +337,7 @@ struct PairRing {
     unsigned smem_addr, row_bytes;
     unsigned voff[NPW];  // this lane's byte offset inside the tile, per load
     int blk_lds[NPW];    // LDS offset of the block relative to buffer A0, per load
-    bool blk_is_b[NPW];
+    u32x4 blk_desc[NPW]; // descriptor of the tensor the block belongs to, per load
 
     DEVINL PairRing(const bf16* a, const bf16* b, unsigned bytes, unsigned row_bytes_, char* smem_, int wave, int lane)
         : a_buf(a, bytes), b_buf(b, bytes), smem(smem_), smem_addr(lds_address(smem_)), row_bytes(row_bytes_)
@@ -336,10 +345,11 @@ struct PairRing {
 #pragma unroll
         for (int j = 0; j < NPW; ++j) {
             const int blk = min(wave + NW * j, NBLK - 1);
-            blk_is_b[j] = blk >= NTI;
-            const int tb = blk_is_b[j] ? blk - NTI : blk;
+            const bool is_b = blk >= NTI;
+            const int tb = is_b ? blk - NTI : blk;
             voff[j] = padded_block_voff<D>(tb, lane, row_bytes);
-            blk_lds[j] = (blk_is_b[j] ? NBUF * TILE_BYTES : 0) + tb * 1024;
+            blk_lds[j] = (is_b ? NBUF * TILE_BYTES : 0) + tb * 1024;
+            blk_desc[j] = pick(is_b, b_buf, a_buf).words;
         }
     }
     DEVINL const char* a_tile(int ti) const { return smem + (ti & (NBUF - 1)) * TILE_BYTES; }
@@ -348,7 +358,9 @@ struct PairRing {
     DEVINL void fetch(int ti, int j) const
     {
         const unsigned dst = smem_addr + (ti & (NBUF - 1)) * TILE_BYTES + blk_lds[j];
-        load_to_lds16(blk_is_b[j] ? b_buf : a_buf, dst, voff[j] + (unsigned)ti * ROWS * row_bytes);
+        RawBuffer d = a_buf;
+        d.words = blk_desc[j];
+        load_to_lds16(d, dst, voff[j] + (unsigned)ti * ROWS * row_bytes);
     }
     DEVINL void fetch_pair(int ti) const
     {
@@ -359,6 +371,84 @@ struct PairRing {
     // meet the other wavefronts: after it, every pair but the IN_FLIGHT most recently requested ones
     // is in LDS.  DRAIN also waits for this wavefront's outstanding LDS reads.  (Plain instructions
     // instead of __syncthreads(): its fences would wait for ALL loads.)
+    template <bool DRAIN, int IN_FLIGHT = 1>
+    DEVINL static void landed_barrier()
+    {
+        if constexpr (DRAIN)
+            asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(IN_FLIGHT * NPW) : "memory");
+        else
+            asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(IN_FLIGHT * NPW) : "memory");
+    }
+};
+
+// ---------------------------------------------------------------------------------------------
+// Ring of NBUF (A tile | B tile | per-row scalars) buffers in LDS for the key-stationary backward
+// pass: A = Q rows, B = dO rows (64 rows each, padded row layout), scalars = one 1 KB block holding
+// x[64] then y[64] floats (the rest unused), where x and y are two arrays of `npad` floats each,
+// stored one after the other in global memory (LSE*log2e and -delta as the dQ pass leaves them).
+// Filled by LDS-direct loads like PairRing: the 2*NTI+1 blocks of a buffer are dealt round robin to
+// the wavefronts, NPW loads per wavefront and buffer.  Tiles past the end arrive as zeros.
+// ---------------------------------------------------------------------------------------------
+template <int D, int NW, int NBUF>
+struct RowsAndScalarsRing {
+    static constexpr int ROWS = 64;
+    static constexpr int STRIDE = tile_stride<D>();
+    static constexpr int TILE_BYTES = ROWS * STRIDE;
+    static_assert(TILE_BYTES % 1024 == 0, "a tile must be a whole number of 1 KB blocks");
+    static_assert((NBUF & (NBUF - 1)) == 0, "ring size must be a power of two");
+    static constexpr int NTI = TILE_BYTES / 1024, NBLK = 2 * NTI + 1, NPW = (NBLK + NW - 1) / NW;
+    static constexpr int OFF_B = TILE_BYTES, OFF_SCALARS = 2 * TILE_BYTES;
+    static constexpr int BUF_BYTES = 2 * TILE_BYTES + 1024;
+    static constexpr int LDS_BYTES = NBUF * BUF_BYTES;
+
+    RawBuffer a_buf, b_buf, s_buf;
+    char* smem;
+    unsigned smem_addr;
+    int ntiles;
+    unsigned voff[NPW];   // this lane's byte offset for tile 0, per load
+    unsigned vstep[NPW];  // what a step to the next tile adds to it
+    int blk_lds[NPW];     // LDS offset of the block inside a buffer
+    int blk_kind[NPW];    // 0 A rows, 1 B rows, 2 scalars
+    u32x4 blk_desc[NPW];  // descriptor of the array the block comes from, per load
+
+    DEVINL RowsAndScalarsRing(const bf16* a, const bf16* b, unsigned bytes, unsigned row_bytes, const float* scalars,
+                              int npad, int ntiles_, char* smem_, int wave, int lane)
+        : a_buf(a, bytes), b_buf(b, bytes), s_buf(scalars, 2u * npad * 4u), smem(smem_), smem_addr(lds_address(smem_)),
+          ntiles(ntiles_)
+    {
+#pragma unroll
+        for (int j = 0; j < NPW; ++j) {
+            const int blk = min(wave + NW * j, NBLK - 1);
+            blk_kind[j] = blk < NTI ? 0 : blk < 2 * NTI ? 1 : 2;
+            const int tb = blk - blk_kind[j] * NTI;
+            blk_lds[j] = blk * 1024;  // A blocks, then B blocks, then the scalars: contiguous
+            blk_desc[j] = pick(blk_kind[j] == 0, a_buf, pick(blk_kind[j] == 1, b_buf, s_buf)).words;
+            if (blk_kind[j] == 2) {
+                voff[j] = lane < 16 ? (unsigned)lane * 16 : lane < 32 ? (unsigned)(npad * 4 + (lane - 16) * 16) : kOutOfRangeBase;
+                vstep[j] = ROWS * 4;
+            } else {
+                voff[j] = padded_block_voff<D>(tb, lane, row_bytes);
+                vstep[j] = ROWS * row_bytes;
+            }
+        }
+    }
+    DEVINL const char* buf(int ti) const { return smem + (ti & (NBUF - 1)) * BUF_BYTES; }
+    // load j (0 <= j < NPW) of this wavefront for tile `ti`
+    DEVINL void fetch(int ti, int j) const
+    {
+        const unsigned dst = smem_addr + (ti & (NBUF - 1)) * BUF_BYTES + blk_lds[j];
+        const unsigned off = voff[j] + (unsigned)ti * vstep[j];
+        // the two scalar arrays follow one another, so running past the first would read the second
+        const bool past_end = blk_kind[j] == 2 && ti >= ntiles;
+        RawBuffer d = a_buf;
+        d.words = blk_desc[j];
+        load_to_lds16(d, dst, past_end ? kOutOfRangeBase : off);
+    }
+    DEVINL void fetch_tile(int ti) const
+    {
+#pragma unroll
+        for (int j = 0; j < NPW; ++j) fetch(ti, j);
+    }
     template <bool DRAIN, int IN_FLIGHT = 1>
     DEVINL static void landed_barrier()
     {
