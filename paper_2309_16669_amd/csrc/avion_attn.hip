@@ -37,15 +37,6 @@ int check_shape(int B, int H, int N, int d, float scale)
     return AVION_OK;
 }
 
-// Tuning knob for sweeps: AVION_VARIANT_<NAME>=<int> picks a kernel instance; unset = default.
-int variant(const char* name, int dflt)
-{
-    char key[64];
-    std::snprintf(key, sizeof key, "AVION_VARIANT_%s", name);
-    const char* s = std::getenv(key);
-    return s ? std::atoi(s) : dflt;
-}
-
 // Workgroups are launched in multiples of 8 (one per XCD); the padding ones exit at once.
 bool grid_for(long long nblocks, unsigned* grid)
 {
@@ -61,38 +52,21 @@ hipError_t allow_lds(K kernel, int bytes)
     return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
 }
 
-template <int D, int QT, int NW>
+template <int D, int NW>
 int launch_fwd(const bf16* q, const bf16* k, const bf16* v, bf16* o, float* lse, int B, int H, int N, float scale,
                hipStream_t st)
 {
-    using Cfg = FwdCfg<D, QT, NW>;
-    static hipError_t attr = allow_lds(avion_fwd_kernel<D, QT, NW>, Cfg::LDS_BYTES);
+    using Cfg = FwdCfg<D, NW>;
+    static hipError_t attr = allow_lds(avion_fwd_kernel<D, NW>, Cfg::LDS_BYTES);
     if (attr != hipSuccess) return hip_fail(attr, "hipFuncSetAttribute(fwd)");
     const int nqb = (N + Cfg::BM - 1) / Cfg::BM;
     const long long nblocks = (long long)nqb * B * H;
     unsigned grid;
     if (!grid_for(nblocks, &grid)) return AVION_EUNSUPPORTED;
-    hipLaunchKernelGGL((avion_fwd_kernel<D, QT, NW>), dim3(grid), dim3(Cfg::NT), Cfg::LDS_BYTES, st, q, k, v, o, lse, H,
-                       N, nqb, (int)nblocks, scale * kLog2e);
+    hipLaunchKernelGGL((avion_fwd_kernel<D, NW>), dim3(grid), dim3(Cfg::NT), Cfg::LDS_BYTES, st, q, k, v, o, lse, H, N, nqb,
+                       (int)nblocks, scale * kLog2e);
     const hipError_t e = hipGetLastError();
     return e == hipSuccess ? AVION_OK : hip_fail(e, "launch avion_fwd_kernel");
-}
-
-template <int D, int NW>
-int launch_fwd_occ(const bf16* q, const bf16* k, const bf16* v, bf16* o, float* lse, int B, int H, int N, float scale,
-                   hipStream_t st)
-{
-    using Cfg = FwdOccCfg<D, NW>;
-    static hipError_t attr = allow_lds(avion_fwd_occ_kernel<D, NW>, Cfg::LDS_BYTES);
-    if (attr != hipSuccess) return hip_fail(attr, "hipFuncSetAttribute(fwd)");
-    const int nqb = (N + Cfg::BM - 1) / Cfg::BM;
-    const long long nblocks = (long long)nqb * B * H;
-    unsigned grid;
-    if (!grid_for(nblocks, &grid)) return AVION_EUNSUPPORTED;
-    hipLaunchKernelGGL((avion_fwd_occ_kernel<D, NW>), dim3(grid), dim3(Cfg::NT), Cfg::LDS_BYTES, st, q, k, v, o, lse, H, N,
-                       nqb, (int)nblocks, scale * kLog2e);
-    const hipError_t e = hipGetLastError();
-    return e == hipSuccess ? AVION_OK : hip_fail(e, "launch avion_fwd_occ_kernel");
 }
 
 template <int D, int NW>
@@ -113,23 +87,6 @@ int launch_dq(const bf16* q, const bf16* k, const bf16* v, const bf16* o, const 
 }
 
 template <int D, int NW>
-int launch_dq_occ(const bf16* q, const bf16* k, const bf16* v, const bf16* o, const bf16* dO, const float* lse, bf16* dq,
-                  float* rowsc, int B, int H, int N, float scale, hipStream_t st)
-{
-    using Cfg = DqOccCfg<D, NW>;
-    static hipError_t attr = allow_lds(avion_dq_occ_kernel<D, NW>, Cfg::LDS_BYTES);
-    if (attr != hipSuccess) return hip_fail(attr, "hipFuncSetAttribute(dq)");
-    const int nqb = (N + Cfg::BM - 1) / Cfg::BM;
-    const long long nblocks = (long long)nqb * B * H;
-    unsigned grid;
-    if (!grid_for(nblocks, &grid)) return AVION_EUNSUPPORTED;
-    hipLaunchKernelGGL((avion_dq_occ_kernel<D, NW>), dim3(grid), dim3(Cfg::NT), Cfg::LDS_BYTES, st, q, k, v, o, dO, lse,
-                       dq, rowsc, H, N, nqb, (int)nblocks, scale * kLog2e, scale);
-    const hipError_t e = hipGetLastError();
-    return e == hipSuccess ? AVION_OK : hip_fail(e, "launch avion_dq_occ_kernel");
-}
-
-template <int D, int NW>
 int launch_dkdv(const bf16* q, const bf16* k, const bf16* v, const bf16* dO, const float* rowsc, bf16* dk, bf16* dv,
                 int B, int H, int N, float scale, hipStream_t st)
 {
@@ -140,46 +97,24 @@ int launch_dkdv(const bf16* q, const bf16* k, const bf16* v, const bf16* dO, con
     const long long nblocks = (long long)nkb * B * H;
     unsigned grid;
     if (!grid_for(nblocks, &grid)) return AVION_EUNSUPPORTED;
-    hipLaunchKernelGGL((avion_dkdv_kernel<D, NW>), dim3(grid), dim3(Cfg::NT), Cfg::LDS_BYTES, st, q, k, v, dO, rowsc,
-                       dk, dv, H, N, nkb, (int)nblocks, scale * kLog2e, scale);
+    hipLaunchKernelGGL((avion_dkdv_kernel<D, NW>), dim3(grid), dim3(Cfg::NT), Cfg::LDS_BYTES, st, q, k, v, dO, rowsc, dk,
+                       dv, H, N, nkb, (int)nblocks, scale * kLog2e, scale);
     const hipError_t e = hipGetLastError();
     return e == hipSuccess ? AVION_OK : hip_fail(e, "launch avion_dkdv_kernel");
 }
 
-template <int D, int NW>
-int launch_dkdv_occ(const bf16* q, const bf16* k, const bf16* v, const bf16* dO, const float* rowsc, bf16* dk, bf16* dv,
-                    int B, int H, int N, float scale, hipStream_t st)
-{
-    using Cfg = DkvOccCfg<D, NW>;
-    static hipError_t attr = allow_lds(avion_dkdv_occ_kernel<D, NW>, Cfg::LDS_BYTES);
-    if (attr != hipSuccess) return hip_fail(attr, "hipFuncSetAttribute(dkdv)");
-    const int nkb = (N + Cfg::BNK - 1) / Cfg::BNK;
-    const long long nblocks = (long long)nkb * B * H;
-    unsigned grid;
-    if (!grid_for(nblocks, &grid)) return AVION_EUNSUPPORTED;
-    hipLaunchKernelGGL((avion_dkdv_occ_kernel<D, NW>), dim3(grid), dim3(Cfg::NT), Cfg::LDS_BYTES, st, q, k, v, dO, rowsc,
-                       dk, dv, H, N, nkb, (int)nblocks, scale * kLog2e, scale);
-    const hipError_t e = hipGetLastError();
-    return e == hipSuccess ? AVION_OK : hip_fail(e, "launch avion_dkdv_occ_kernel");
-}
-
-// Kernel instances.  Only instances that keep every array in registers (no scratch, no spills) are
-// dispatched; AVION_VARIANT_FWD / AVION_VARIANT_DKDV select the alternatives kept for tuning sweeps.
+// Kernel instances: four wavefronts per workgroup for every kernel and head size.
 template <int D>
 int fwd_dispatch(const bf16* q, const bf16* k, const bf16* v, bf16* o, float* lse, int B, int H, int N, float scale,
                  hipStream_t st)
 {
-    static const int vf = variant("FWD", 0);
-    if (vf == 10) return launch_fwd_occ<D, 4>(q, k, v, o, lse, B, H, N, scale, st);
-    return launch_fwd<D, 1, 4>(q, k, v, o, lse, B, H, N, scale, st);
+    return launch_fwd<D, 4>(q, k, v, o, lse, B, H, N, scale, st);
 }
 
 template <int D>
 int dq_dispatch(const bf16* q, const bf16* k, const bf16* v, const bf16* o, const float* lse, const bf16* dO, bf16* dq,
                 float* rowsc, int B, int H, int N, float scale, hipStream_t st)
 {
-    static const int vq = variant("DQ", 0);
-    if (vq == 10) return launch_dq_occ<D, 4>(q, k, v, o, dO, lse, dq, rowsc, B, H, N, scale, st);
     return launch_dq<D, 4>(q, k, v, o, dO, lse, dq, rowsc, B, H, N, scale, st);
 }
 
@@ -187,8 +122,6 @@ template <int D>
 int dkdv_dispatch(const bf16* q, const bf16* k, const bf16* v, const bf16* dO, bf16* dk, bf16* dv, const float* rowsc,
                   int B, int H, int N, float scale, hipStream_t st)
 {
-    static const int vk = variant("DKDV", 0);
-    if (vk == 10) return launch_dkdv_occ<D, 4>(q, k, v, dO, rowsc, dk, dv, B, H, N, scale, st);
     return launch_dkdv<D, 4>(q, k, v, dO, rowsc, dk, dv, B, H, N, scale, st);
 }
 
@@ -253,12 +186,12 @@ int avion_attn_bwd_dq(const void* q, const void* k, const void* v, const void* o
         if (!aligned16(p)) return AVION_EUNSUPPORTED;
     if (!workspace_ok(workspace, workspace_bytes, B, H, N, d)) return AVION_EWORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    float* delta = static_cast<float*>(workspace);
+    float* rowsc = static_cast<float*>(workspace);  // receives LSE*log2e and -delta for the second pass
     const bf16 *qq = static_cast<const bf16*>(q), *kk = static_cast<const bf16*>(k), *vv = static_cast<const bf16*>(v),
                *oo = static_cast<const bf16*>(o), *gg = static_cast<const bf16*>(dO);
     bf16* dqq = static_cast<bf16*>(dq);
-    if (d == 64) return dq_dispatch<64>(qq, kk, vv, oo, lse, gg, dqq, delta, B, H, N, scale, st);
-    return dq_dispatch<80>(qq, kk, vv, oo, lse, gg, dqq, delta, B, H, N, scale, st);
+    if (d == 64) return dq_dispatch<64>(qq, kk, vv, oo, lse, gg, dqq, rowsc, B, H, N, scale, st);
+    return dq_dispatch<80>(qq, kk, vv, oo, lse, gg, dqq, rowsc, B, H, N, scale, st);
 }
 
 int avion_attn_bwd_dkdv(const void* q, const void* k, const void* v, const float* lse, const void* dO, void* dk,

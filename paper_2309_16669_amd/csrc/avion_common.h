@@ -59,13 +59,11 @@ DEVINL f32x16 f32x16_zero()
 
 DEVINL bf16x8 as_bf16x8(u32x4 x) { return __builtin_bit_cast(bf16x8, x); }
 
-// max of three without the NaN-quieting moves the generic fmaxf lowering adds in front
-DEVINL float max3(float a, float b, float c)
-{
-    float r;
-    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
-    return r;
-}
+// Max of three.  Deliberately plain fmaxf, not inline assembly: the compiler inserts the wait states
+// that a vector instruction needs before it may read an MFMA result (or feed a lane permute) only
+// around instructions it knows, and an opaque asm statement reading an accumulator right after the
+// MFMA that produces it picks up stale registers every now and then.  Only used outside hot loops.
+DEVINL float max3(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
 // Exchange between the two halves of the wavefront (lane l <-> lane l^32) with v_permlane32_swap.
 // The instruction swaps the upper half of its first register with the lower half of its second;
 // fed with two copies of x it leaves, in every lane, the lower-half lane's value in the first
@@ -174,7 +172,7 @@ constexpr unsigned kOutOfRangeBase = 0x80000000u;
 // lane i fetches from byte offset `voff` of the buffer land at LDS address lds_addr + 16*i, so one
 // instruction fills 1 KB of LDS; lds_addr (it travels in M0) must be the same in all lanes.
 // Offsets beyond the buffer deposit zeros.  Completion is tracked by the vector-memory counter
-// (s_waitcnt vmcnt), like any other load.
+// (s_waitcnt vmcnt) for the fetch and by lgkmcnt for the write into LDS.
 // Written as inline assembly on purpose: told that an instruction writes LDS asynchronously, the
 // compiler makes every later LDS read wait for ALL outstanding loads, which would serialise the
 // prefetch; here the ordering is established by hand (vmcnt waits + workgroup barriers).
@@ -188,6 +186,7 @@ struct RawBuffer {
         words[2] = __builtin_amdgcn_readfirstlane(bytes);
         words[3] = 0x00020000u;
     }
+    DEVINL explicit RawBuffer(u32x4 w) : words(w) {}
 };
 DEVINL unsigned lds_address(const char* p) { return (unsigned)(unsigned long)(const lds_char*)p; }
 // one of two / three descriptors, chosen by a wavefront-uniform condition; the result is moved to
@@ -266,30 +265,25 @@ struct TileStage {
     static constexpr int BYTES = R * STRIDE;
     u32x4 r[PER];
 
-    // piece i (0 <= i < PER) of the tile: one 16-byte load / store per thread
-    DEVINL void load_piece(const SliceView& src, int r0, int tid, int i)
-    {
-        const int idx = tid + i * NT;
-        const int row = idx / CH, ch = idx % CH;
-        unsigned off = (unsigned)(r0 + row) * src.row_bytes + ch * 16;
-        if (TOTAL % NT != 0 && idx >= TOTAL) off = kOutOfRange;
-        r[i] = src.load16(off);
-    }
-    DEVINL void store_piece(char* tile, int tid, int i) const
-    {
-        const int idx = tid + i * NT;
-        const int row = idx / CH, ch = idx % CH;
-        if (TOTAL % NT == 0 || idx < TOTAL) *reinterpret_cast<u32x4*>(tile + row * STRIDE + ch * 16) = r[i];
-    }
     DEVINL void load(const SliceView& src, int r0, int tid)
     {
 #pragma unroll
-        for (int i = 0; i < PER; ++i) load_piece(src, r0, tid, i);
+        for (int i = 0; i < PER; ++i) {
+            const int idx = tid + i * NT;
+            const int row = idx / CH, ch = idx % CH;
+            unsigned off = (unsigned)(r0 + row) * src.row_bytes + ch * 16;
+            if (TOTAL % NT != 0 && idx >= TOTAL) off = kOutOfRange;
+            r[i] = src.load16(off);
+        }
     }
     DEVINL void store(char* tile, int tid) const
     {
 #pragma unroll
-        for (int i = 0; i < PER; ++i) store_piece(tile, tid, i);
+        for (int i = 0; i < PER; ++i) {
+            const int idx = tid + i * NT;
+            const int row = idx / CH, ch = idx % CH;
+            if (TOTAL % NT == 0 || idx < TOTAL) *reinterpret_cast<u32x4*>(tile + row * STRIDE + ch * 16) = r[i];
+        }
     }
     // the pad of every row reads as zeros (only D = 80 ever reads it)
     DEVINL static void zero_pad(char* tile, int tid)
@@ -313,149 +307,81 @@ DEVINL f32x16 key_mask_block(int key_base, int g, int N)
 }
 
 // ---------------------------------------------------------------------------------------------
-// Ring of NBUF (A tile | B tile) pairs in LDS, each tile 64 token rows of D channels in the padded
-// row layout above, filled straight from global memory by LDS-direct loads: buffers A0.. then B0..
-// A tile is a sequence of 1 KB blocks, each filled by one load of one wavefront (a block holds 64
-// consecutive 16-byte chunks of the padded rows; lanes that land on a pad chunk deposit zeros).
-// The 2*NTI blocks of a pair are dealt round robin: wavefront w issues blocks w, w+NW, ...; where
-// the list runs out a wavefront repeats the last block, so that all issue the same number NPW of
-// loads per pair -- which is what lets every wavefront wait with the same vmcnt value.
-// Tiles past the end of the sequence arrive as zero rows.
+// Ring of NBUF buffers in LDS, each holding an A tile and a B tile of 64 token rows in the padded
+// row layout above (K and V, or Q and dO) and, with SCALARS, one more 1 KB block with x[64] then
+// y[64] floats, where x and y are two arrays of `npad` floats stored one after the other in global
+// memory (LSE*log2e and -delta as the dQ pass leaves them).  Buffers are filled straight from
+// global memory by LDS-direct loads: a buffer is a sequence of 1 KB blocks (A blocks, B blocks,
+// scalars), each filled by one load of one wavefront; a block of a tile holds 64 consecutive
+// 16-byte chunks of its padded rows, and lanes that land on a pad chunk deposit zeros.  Blocks are
+// dealt round robin: wavefront w issues blocks w, w+NW, ...  Tiles past the end of the sequence
+// arrive as zero rows.
 // ---------------------------------------------------------------------------------------------
-template <int D, int NW, int NBUF = 4>
-struct PairRing {
-    static constexpr int ROWS = 64;
-    static constexpr int STRIDE = tile_stride<D>();
-    static constexpr int TILE_BYTES = ROWS * STRIDE;
-    static_assert(TILE_BYTES % 1024 == 0, "a tile must be a whole number of 1 KB blocks");
-    static constexpr int NTI = TILE_BYTES / 1024, NBLK = 2 * NTI, NPW = (NBLK + NW - 1) / NW;
-    static_assert((NBUF & (NBUF - 1)) == 0, "ring size must be a power of two");
-    static constexpr int LDS_BYTES = 2 * NBUF * TILE_BYTES;
-
-    RawBuffer a_buf, b_buf;
-    char* smem;
-    unsigned smem_addr, row_bytes;
-    unsigned voff[NPW];  // this lane's byte offset inside the tile, per load
-    int blk_lds[NPW];    // LDS offset of the block relative to buffer A0, per load
-    u32x4 blk_desc[NPW]; // descriptor of the tensor the block belongs to, per load
-
-    DEVINL PairRing(const bf16* a, const bf16* b, unsigned bytes, unsigned row_bytes_, char* smem_, int wave, int lane)
-        : a_buf(a, bytes), b_buf(b, bytes), smem(smem_), smem_addr(lds_address(smem_)), row_bytes(row_bytes_)
-    {
-#pragma unroll
-        for (int j = 0; j < NPW; ++j) {
-            const int blk = min(wave + NW * j, NBLK - 1);
-            const bool is_b = blk >= NTI;
-            const int tb = is_b ? blk - NTI : blk;
-            voff[j] = padded_block_voff<D>(tb, lane, row_bytes);
-            blk_lds[j] = (is_b ? NBUF * TILE_BYTES : 0) + tb * 1024;
-            blk_desc[j] = pick(is_b, b_buf, a_buf).words;
-        }
-    }
-    DEVINL const char* a_tile(int ti) const { return smem + (ti & (NBUF - 1)) * TILE_BYTES; }
-    DEVINL const char* b_tile(int ti) const { return smem + (NBUF + (ti & (NBUF - 1))) * TILE_BYTES; }
-    // load j (0 <= j < NPW) of this wavefront for pair `ti`
-    DEVINL void fetch(int ti, int j) const
-    {
-        const unsigned dst = smem_addr + (ti & (NBUF - 1)) * TILE_BYTES + blk_lds[j];
-        RawBuffer d = a_buf;
-        d.words = blk_desc[j];
-        load_to_lds16(d, dst, voff[j] + (unsigned)ti * ROWS * row_bytes);
-    }
-    DEVINL void fetch_pair(int ti) const
-    {
-#pragma unroll
-        for (int j = 0; j < NPW; ++j) fetch(ti, j);
-    }
-    // Wait until at most IN_FLIGHT pairs' worth of this wavefront's loads is still outstanding, then
-    // meet the other wavefronts: after it, every pair but the IN_FLIGHT most recently requested ones
-    // is in LDS.  DRAIN also waits for this wavefront's outstanding LDS reads.  (Plain instructions
-    // instead of __syncthreads(): its fences would wait for ALL loads.)
-    template <bool DRAIN, int IN_FLIGHT = 1>
-    DEVINL static void landed_barrier()
-    {
-        if constexpr (DRAIN)
-            asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(IN_FLIGHT * NPW) : "memory");
-        else
-            asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(IN_FLIGHT * NPW) : "memory");
-    }
-};
-
-// ---------------------------------------------------------------------------------------------
-// Ring of NBUF (A tile | B tile | per-row scalars) buffers in LDS for the key-stationary backward
-// pass: A = Q rows, B = dO rows (64 rows each, padded row layout), scalars = one 1 KB block holding
-// x[64] then y[64] floats (the rest unused), where x and y are two arrays of `npad` floats each,
-// stored one after the other in global memory (LSE*log2e and -delta as the dQ pass leaves them).
-// Filled by LDS-direct loads like PairRing: the 2*NTI+1 blocks of a buffer are dealt round robin to
-// the wavefronts, NPW loads per wavefront and buffer.  Tiles past the end arrive as zeros.
-// ---------------------------------------------------------------------------------------------
-template <int D, int NW, int NBUF>
-struct RowsAndScalarsRing {
+template <int D, int NW, int NBUF, bool SCALARS>
+struct TileRing {
     static constexpr int ROWS = 64;
     static constexpr int STRIDE = tile_stride<D>();
     static constexpr int TILE_BYTES = ROWS * STRIDE;
     static_assert(TILE_BYTES % 1024 == 0, "a tile must be a whole number of 1 KB blocks");
     static_assert((NBUF & (NBUF - 1)) == 0, "ring size must be a power of two");
-    static constexpr int NTI = TILE_BYTES / 1024, NBLK = 2 * NTI + 1, NPW = (NBLK + NW - 1) / NW;
+    static constexpr int NTI = TILE_BYTES / 1024, NBLK = 2 * NTI + (SCALARS ? 1 : 0), NPW = (NBLK + NW - 1) / NW;
     static constexpr int OFF_B = TILE_BYTES, OFF_SCALARS = 2 * TILE_BYTES;
-    static constexpr int BUF_BYTES = 2 * TILE_BYTES + 1024;
+    static constexpr int BUF_BYTES = NBLK * 1024;
     static constexpr int LDS_BYTES = NBUF * BUF_BYTES;
 
-    RawBuffer a_buf, b_buf, s_buf;
     char* smem;
     unsigned smem_addr;
-    int ntiles;
-    unsigned voff[NPW];   // this lane's byte offset for tile 0, per load
+    int ntiles, wave;
+    // per load j of this wavefront (block wave + NW*j, if there is one):
+    bool has[NPW];        // the block exists
+    bool is_scalars[NPW];
+    unsigned voff[NPW];   // this lane's byte offset for tile 0
     unsigned vstep[NPW];  // what a step to the next tile adds to it
-    int blk_lds[NPW];     // LDS offset of the block inside a buffer
-    int blk_kind[NPW];    // 0 A rows, 1 B rows, 2 scalars
-    u32x4 blk_desc[NPW];  // descriptor of the array the block comes from, per load
+    u32x4 desc[NPW];      // descriptor of the array the block comes from
 
-    DEVINL RowsAndScalarsRing(const bf16* a, const bf16* b, unsigned bytes, unsigned row_bytes, const float* scalars,
-                              int npad, int ntiles_, char* smem_, int wave, int lane)
-        : a_buf(a, bytes), b_buf(b, bytes), s_buf(scalars, 2u * npad * 4u), smem(smem_), smem_addr(lds_address(smem_)),
-          ntiles(ntiles_)
+    DEVINL TileRing(const bf16* a, const bf16* b, unsigned bytes, unsigned row_bytes, const float* scalars, int npad,
+                    int ntiles_, char* smem_, int wave_, int lane)
+        : smem(smem_), smem_addr(lds_address(smem_)), ntiles(ntiles_), wave(wave_)
     {
+        const RawBuffer a_buf(a, bytes), b_buf(b, bytes), s_buf(scalars, SCALARS ? 2u * npad * 4u : 0u);
 #pragma unroll
         for (int j = 0; j < NPW; ++j) {
-            const int blk = min(wave + NW * j, NBLK - 1);
-            blk_kind[j] = blk < NTI ? 0 : blk < 2 * NTI ? 1 : 2;
-            const int tb = blk - blk_kind[j] * NTI;
-            blk_lds[j] = blk * 1024;  // A blocks, then B blocks, then the scalars: contiguous
-            blk_desc[j] = pick(blk_kind[j] == 0, a_buf, pick(blk_kind[j] == 1, b_buf, s_buf)).words;
-            if (blk_kind[j] == 2) {
+            const int blk = wave + NW * j;
+            has[j] = blk < NBLK;
+            const int kind = blk < NTI ? 0 : blk < 2 * NTI ? 1 : 2;
+            is_scalars[j] = SCALARS && kind == 2;
+            if (is_scalars[j]) {
                 voff[j] = lane < 16 ? (unsigned)lane * 16 : lane < 32 ? (unsigned)(npad * 4 + (lane - 16) * 16) : kOutOfRangeBase;
                 vstep[j] = ROWS * 4;
             } else {
-                voff[j] = padded_block_voff<D>(tb, lane, row_bytes);
+                voff[j] = padded_block_voff<D>(blk - kind * NTI, lane, row_bytes);
                 vstep[j] = ROWS * row_bytes;
             }
+            desc[j] = pick(kind == 0, a_buf, pick(kind == 1, b_buf, s_buf)).words;
         }
     }
     DEVINL const char* buf(int ti) const { return smem + (ti & (NBUF - 1)) * BUF_BYTES; }
-    // load j (0 <= j < NPW) of this wavefront for tile `ti`
-    DEVINL void fetch(int ti, int j) const
-    {
-        const unsigned dst = smem_addr + (ti & (NBUF - 1)) * BUF_BYTES + blk_lds[j];
-        const unsigned off = voff[j] + (unsigned)ti * vstep[j];
-        // the two scalar arrays follow one another, so running past the first would read the second
-        const bool past_end = blk_kind[j] == 2 && ti >= ntiles;
-        RawBuffer d = a_buf;
-        d.words = blk_desc[j];
-        load_to_lds16(d, dst, past_end ? kOutOfRangeBase : off);
-    }
-    DEVINL void fetch_tile(int ti) const
+    // request tile `ti` (this wavefront's share of its blocks)
+    DEVINL void fetch(int ti) const
     {
 #pragma unroll
-        for (int j = 0; j < NPW; ++j) fetch(ti, j);
+        for (int j = 0; j < NPW; ++j) {
+            if (!has[j]) continue;
+            const unsigned dst = smem_addr + (ti & (NBUF - 1)) * BUF_BYTES + (wave + NW * j) * 1024;
+            // the two scalar arrays follow one another, so running past the first would read the second
+            const bool past_end = is_scalars[j] && ti >= ntiles;
+            load_to_lds16(RawBuffer(desc[j]), dst, past_end ? kOutOfRangeBase : voff[j] + (unsigned)ti * vstep[j]);
+        }
     }
-    template <bool DRAIN, int IN_FLIGHT = 1>
+    // Wait for all of this wavefront's requests, then meet the other wavefronts: after it every
+    // requested tile is in LDS, and every wavefront is past the code before the barrier.  An
+    // LDS-direct load counts in both counters -- vmcnt for the fetch, then lgkmcnt for the deposit
+    // into LDS, hence two waits in this order -- and only when both have drained is the data visible
+    // to other wavefronts.  (Plain
+    // instructions: to the compiler the loads above are opaque, so no fence would wait for them.)
     DEVINL static void landed_barrier()
     {
-        if constexpr (DRAIN)
-            asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(IN_FLIGHT * NPW) : "memory");
-        else
-            asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(IN_FLIGHT * NPW) : "memory");
+        asm volatile("s_waitcnt vmcnt(0)\n\ts_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
     }
 };
 

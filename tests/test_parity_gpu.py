@@ -69,15 +69,19 @@ def test_full_size_configs_on_sampled_heads(name):
     assert np.sqrt(((dv_sum - do_sum) ** 2).sum() / (do_sum ** 2).sum()) <= 2e-3
 
 
-def test_bitwise_reproducible():
+@pytest.mark.parametrize("shape", [(2, 3, 700, 64), (1, 4, 1568, 64), (2, 2, 300, 80)])
+def test_bitwise_reproducible(shape):
+    # no atomics and no order-dependent reductions: repeated runs agree bit for bit (this is also
+    # what exposes a tile that is read before it has completely arrived)
     import torch
-    w = si.small_workload(2, 3, 700, 64, seed=31337)
+    w = si.small_workload(*shape, seed=31337)
     x = si.make_inputs(w)
     a = gh.run_hip(w, x)
-    b = gh.run_hip(w, x)
-    for n in a:
-        assert torch.equal(a[n].view(torch.int16) if a[n].dtype == torch.bfloat16 else a[n],
-                           b[n].view(torch.int16) if b[n].dtype == torch.bfloat16 else b[n]), n
+    for _ in range(3):
+        b = gh.run_hip(w, x)
+        for n in a:
+            assert torch.equal(a[n].view(torch.int16) if a[n].dtype == torch.bfloat16 else a[n],
+                               b[n].view(torch.int16) if b[n].dtype == torch.bfloat16 else b[n]), n
 
 
 def test_identical_keys_and_single_token_closed_forms_on_gpu():
