@@ -86,6 +86,9 @@ def main():
                     help="recipe = the synthetic N(0,1) inputs the metric is quoted on; zeros / ones = constant "
                          "operands, same instruction stream and traffic, to show how much of the time is the "
                          "data-dependent clock throttling of the chip (never the reported configuration)")
+    ap.add_argument("--layout", choices=("separate", "packed"), default="separate",
+                    help="separate = q, k, v as three [B,N,H,d] tensors (the reported configuration); packed = one "
+                         "[B,N,3,H,d] tensor through the *_qkvpacked entry points (same kernels, token stride 3*H*d)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain device copy of Q (known size) so that HBM counters of a "
                          "rocprofv3 --pmc run can be scaled")
@@ -143,6 +146,17 @@ def main():
     def bwd_dkdv():
         av.attn_bwd_dkdv(q, k, v, lse, dO, dk, dv, w.scale, ws, stream)
 
+    packed = args.layout == "packed"
+    if packed:
+        qkv = torch.stack((q, k, v), dim=2).contiguous()
+        dqkv = torch.empty_like(qkv)
+
+        def fwd():
+            av.attn_fwd_qkvpacked(qkv, o, lse, w.scale, stream)
+
+        def bwd():
+            av.attn_bwd_qkvpacked(qkv, o, lse, dO, dqkv, w.scale, ws, stream)
+
     def step():
         fwd()
         bwd()
@@ -159,9 +173,15 @@ def main():
 
     # per-phase times with HIP events on the launch stream
     ms_fwd = timed(fwd, args.steps, 2, stream)
-    ms_dq = timed(bwd_dq, args.steps, 2, stream)
-    ms_dkdv = timed(bwd_dkdv, args.steps, 2, stream)
     ms_bwd = timed(bwd, args.steps, 2, stream)
+    if packed:
+        # the packed call has no separate phases: split its time in the proportion of the two kernels
+        # on the separate layout (same kernels)
+        a, b = timed(bwd_dq, args.steps, 2, stream), timed(bwd_dkdv, args.steps, 2, stream)
+        ms_dq, ms_dkdv = ms_bwd * a / (a + b), ms_bwd * b / (a + b)
+    else:
+        ms_dq = timed(bwd_dq, args.steps, 2, stream)
+        ms_dkdv = timed(bwd_dkdv, args.steps, 2, stream)
 
     base = w.base
     tf = lambda flops, ms: flops / (ms * 1e-3) / 1e12
@@ -181,7 +201,7 @@ def main():
         "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic" if args.operands == "recipe" else f"constant operands ({args.operands}), diagnostic only",
         "config": {"workload": f"{w.name}: B={w.B} H={w.H} N={w.N} d={w.d} non-causal, scale={w.scale:g}, "
-                               "Q/K/V/dO ~ N(0,1) bf16, fwd+bwd"},
+                               "Q/K/V/dO ~ N(0,1) bf16, fwd+bwd" + (", packed [B,N,3,H,d] QKV" if packed else "")},
         "pct_of_bf16_mfma_peak": 100.0 * value / PEAK_BF16_TFLOPS,
         "phases": {
             "fwd": {"ms": ms_fwd, "tflops": tf(4 * base, ms_fwd), "pct_peak": 100 * tf(4 * base, ms_fwd) / PEAK_BF16_TFLOPS},

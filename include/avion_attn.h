@@ -21,8 +21,8 @@
  *   - Every tensor pointer must be 16-byte aligned.  Outputs must not alias inputs or each other.
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls only enqueue work
  *     on that stream and return; they never synchronise.
- *   - Supported head dims: d = 64 and d = 80.  Any B, H, N >= 1 with N <= 2^24, B*H <= 2^24 and
- *     fewer than 2^31 workgroups (see AVION_EUNSUPPORTED below).
+ *   - Supported head dims: d = 64 and d = 80.  Any B, H, N >= 1 with N <= 2^24, B*H <= 2^24,
+ *     (N + 256) * H*d * 2 bytes < 2^31 and fewer than 2^31 workgroups (else AVION_EUNSUPPORTED).
  *   - Return value: AVION_OK (0) or a negative AVION_E* code.  On an argument error nothing is
  *     launched and no output is touched.  No exception crosses the boundary.
  *   - NaN/Inf in the inputs are not checked and propagate.
@@ -110,6 +110,28 @@ int avion_attn_bwd_dq(const void *q, const void *k, const void *v, const void *o
 int avion_attn_bwd_dkdv(const void *q, const void *k, const void *v, const float *lse,
                         const void *dO, void *dk, void *dv, int B, int H, int N, int d, float scale,
                         const void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Packed-QKV variants: the attention of an encoder layer sits right after the layer's joint
+ * query/key/value projection (Sec. 3, "Video Transformer": each layer is a multi-head
+ * self-attention on the N tokens), whose output is one tensor.  These take that tensor as it is,
+ * so no copy splits it first, and return the gradient in the same packing, ready for the
+ * projection's backward.
+ *   qkv   : in,  bf16 [B,N,3,H,d] contiguous: plane 0 = queries, 1 = keys, 2 = values
+ *           (token stride 3*H*d elements, plane stride H*d, head stride d)
+ *   o, dO : bf16 [B,N,H,d];  lse : fp32 [B,H,N]   (as in the unpacked calls)
+ *   dqkv  : out, bf16 [B,N,3,H,d], fully overwritten (planes dQ, dK, dV); must not alias qkv
+ * Everything else -- alignment, workspace (same size as avion_attn_bwd_workspace_bytes), stream,
+ * errors, arithmetic -- is as in avion_attn_fwd / avion_attn_bwd; the same kernels run, with a
+ * token stride of 3*H*d for the packed tensors, and give bit-identical results.  The shape limit
+ * becomes (N + 256) * 3*H*d * 2 bytes < 2^31.
+ */
+int avion_attn_fwd_qkvpacked(const void *qkv, void *o, float *lse,
+                             int B, int H, int N, int d, float scale, void *stream);
+
+int avion_attn_bwd_qkvpacked(const void *qkv, const void *o, const float *lse, const void *dO,
+                             void *dqkv, int B, int H, int N, int d, float scale,
+                             void *workspace, size_t workspace_bytes, void *stream);
 
 #ifdef __cplusplus
 }

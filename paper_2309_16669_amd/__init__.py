@@ -1,7 +1,7 @@
 """MI355X-native exact O(N)-memory attention (forward + backward) behind a C ABI.
 
-`attn_fwd`, `attn_bwd`, `attn_bwd_workspace_bytes` mirror the entry points of
-`include/avion_attn.h` one to one.  This module only marshals arguments (device pointers, sizes,
+`attn_fwd`, `attn_bwd`, `attn_bwd_workspace_bytes`, `attn_fwd_qkvpacked`, ... mirror the entry points
+of `include/avion_attn.h` one to one.  This module only marshals arguments (device pointers, sizes,
 the current HIP stream); every step of the computation runs in the HIP kernels of
 `libavion_attn.so`.  There is no CPU or PyTorch fallback: if the library is missing, loading fails.
 PyTorch is used for device memory and streams only.
@@ -51,6 +51,10 @@ def load_library() -> ctypes.CDLL:
         lib.avion_attn_bwd_dq.argtypes = [p, p, p, p, p, p, p, i, i, i, i, f, p, sz, p]
         lib.avion_attn_bwd_dkdv.restype = i
         lib.avion_attn_bwd_dkdv.argtypes = [p, p, p, p, p, p, p, i, i, i, i, f, p, sz, p]
+        lib.avion_attn_fwd_qkvpacked.restype = i
+        lib.avion_attn_fwd_qkvpacked.argtypes = [p, p, p, i, i, i, i, f, p]
+        lib.avion_attn_bwd_qkvpacked.restype = i
+        lib.avion_attn_bwd_qkvpacked.argtypes = [p, p, p, p, p, i, i, i, i, f, p, sz, p]
         _lib = lib
     return _lib
 
@@ -146,3 +150,30 @@ def attn_bwd_dkdv(q, k, v, lse, dO, dk, dv, scale: float, workspace, stream=None
     _check(load_library().avion_attn_bwd_dkdv(_ptr(q), _ptr(k), _ptr(v), _ptr(lse), _ptr(dO), _ptr(dk), _ptr(dv),
                                               B, H, N, d, float(scale), _ptr(workspace), workspace.numel(),
                                               _stream_handle(stream)))
+
+
+def attn_fwd_qkvpacked(qkv, o, lse, scale: float, stream=None) -> None:
+    """avion_attn_fwd_qkvpacked: qkv bf16 [B,N,3,H,d] (the joint projection's output), o bf16 [B,N,H,d],
+    lse fp32 [B,H,N]."""
+    import torch
+    B, N, three, H, d = qkv.shape
+    _require(qkv, "qkv", torch.bfloat16, (B, N, 3, H, d))
+    _require(o, "o", torch.bfloat16, (B, N, H, d))
+    _require(lse, "lse", torch.float32, (B, H, N))
+    _check(load_library().avion_attn_fwd_qkvpacked(_ptr(qkv), _ptr(o), _ptr(lse), B, H, N, d, float(scale),
+                                                   _stream_handle(stream)))
+
+
+def attn_bwd_qkvpacked(qkv, o, lse, dO, dqkv, scale: float, workspace, stream=None) -> None:
+    """avion_attn_bwd_qkvpacked: gradients of the packed tensor, in the same packing."""
+    import torch
+    B, N, three, H, d = qkv.shape
+    for t, n in ((qkv, "qkv"), (dqkv, "dqkv")):
+        _require(t, n, torch.bfloat16, (B, N, 3, H, d))
+    for t, n in ((o, "o"), (dO, "dO")):
+        _require(t, n, torch.bfloat16, (B, N, H, d))
+    _require(lse, "lse", torch.float32, (B, H, N))
+    _require(workspace, "workspace", torch.uint8)
+    _check(load_library().avion_attn_bwd_qkvpacked(_ptr(qkv), _ptr(o), _ptr(lse), _ptr(dO), _ptr(dqkv), B, H, N, d,
+                                                   float(scale), _ptr(workspace), workspace.numel(),
+                                                   _stream_handle(stream)))

@@ -25,7 +25,13 @@ int hip_fail(hipError_t e, const char* what)
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-int check_shape(int B, int H, int N, int d, float scale)
+// Token strides (elements between consecutive tokens of one head) of the two tensor groups.
+struct Strides {
+    int qkv;  // Q, K, V and their gradients: H*d, or 3*H*d when they are packed in one tensor
+    int o;    // O and dO: H*d
+};
+
+int check_shape(int B, int H, int N, int d, float scale, int packed = 1)
 {
     if (B < 1 || H < 1 || N < 1) return AVION_EINVAL;
     if (!(scale > 0.f) || !std::isfinite(scale)) return AVION_EINVAL;
@@ -33,7 +39,7 @@ int check_shape(int B, int H, int N, int d, float scale)
     if (N > (1 << 24) || (long long)B * H > (1 << 24)) return AVION_EUNSUPPORTED;
     // one (batch, head) slice is addressed with 32-bit byte offsets (buffer loads), and tile loads
     // may start up to four 64-row tiles past the end of the sequence
-    if (((long long)N + 256) * H * d * 2 >= (1LL << 31)) return AVION_EUNSUPPORTED;
+    if (((long long)N + 256) * packed * H * d * 2 >= (1LL << 31)) return AVION_EUNSUPPORTED;
     return AVION_OK;
 }
 
@@ -53,8 +59,8 @@ hipError_t allow_lds(K kernel, int bytes)
 }
 
 template <int D, int NW>
-int launch_fwd(const bf16* q, const bf16* k, const bf16* v, bf16* o, float* lse, int B, int H, int N, float scale,
-               hipStream_t st)
+int launch_fwd(const bf16* q, const bf16* k, const bf16* v, bf16* o, float* lse, int B, int H, int N, Strides rs,
+               float scale, hipStream_t st)
 {
     using Cfg = FwdCfg<D, NW>;
     static hipError_t attr = allow_lds(avion_fwd_kernel<D, NW>, Cfg::LDS_BYTES);
@@ -63,15 +69,15 @@ int launch_fwd(const bf16* q, const bf16* k, const bf16* v, bf16* o, float* lse,
     const long long nblocks = (long long)nqb * B * H;
     unsigned grid;
     if (!grid_for(nblocks, &grid)) return AVION_EUNSUPPORTED;
-    hipLaunchKernelGGL((avion_fwd_kernel<D, NW>), dim3(grid), dim3(Cfg::NT), Cfg::LDS_BYTES, st, q, k, v, o, lse, H, N, nqb,
-                       (int)nblocks, scale * kLog2e);
+    hipLaunchKernelGGL((avion_fwd_kernel<D, NW>), dim3(grid), dim3(Cfg::NT), Cfg::LDS_BYTES, st, q, k, v, o, lse, H, N, rs.qkv,
+                       rs.o, nqb, (int)nblocks, scale * kLog2e);
     const hipError_t e = hipGetLastError();
     return e == hipSuccess ? AVION_OK : hip_fail(e, "launch avion_fwd_kernel");
 }
 
 template <int D, int NW>
 int launch_dq(const bf16* q, const bf16* k, const bf16* v, const bf16* o, const bf16* dO, const float* lse, bf16* dq,
-              float* rowsc, int B, int H, int N, float scale, hipStream_t st)
+              float* rowsc, int B, int H, int N, Strides rs, float scale, hipStream_t st)
 {
     using Cfg = DqCfg<D, NW>;
     static hipError_t attr = allow_lds(avion_dq_kernel<D, NW>, Cfg::LDS_BYTES);
@@ -81,14 +87,14 @@ int launch_dq(const bf16* q, const bf16* k, const bf16* v, const bf16* o, const 
     unsigned grid;
     if (!grid_for(nblocks, &grid)) return AVION_EUNSUPPORTED;
     hipLaunchKernelGGL((avion_dq_kernel<D, NW>), dim3(grid), dim3(Cfg::NT), Cfg::LDS_BYTES, st, q, k, v, o, dO, lse, dq,
-                       rowsc, H, N, nqb, (int)nblocks, scale * kLog2e, scale);
+                       rowsc, H, N, rs.qkv, rs.o, nqb, (int)nblocks, scale * kLog2e, scale);
     const hipError_t e = hipGetLastError();
     return e == hipSuccess ? AVION_OK : hip_fail(e, "launch avion_dq_kernel");
 }
 
 template <int D, int NW>
 int launch_dkdv(const bf16* q, const bf16* k, const bf16* v, const bf16* dO, const float* rowsc, bf16* dk, bf16* dv,
-                int B, int H, int N, float scale, hipStream_t st)
+                int B, int H, int N, Strides rs, float scale, hipStream_t st)
 {
     using Cfg = DkvCfg<D, NW>;
     static hipError_t attr = allow_lds(avion_dkdv_kernel<D, NW>, Cfg::LDS_BYTES);
@@ -98,31 +104,25 @@ int launch_dkdv(const bf16* q, const bf16* k, const bf16* v, const bf16* dO, con
     unsigned grid;
     if (!grid_for(nblocks, &grid)) return AVION_EUNSUPPORTED;
     hipLaunchKernelGGL((avion_dkdv_kernel<D, NW>), dim3(grid), dim3(Cfg::NT), Cfg::LDS_BYTES, st, q, k, v, dO, rowsc, dk,
-                       dv, H, N, nkb, (int)nblocks, scale * kLog2e, scale);
+                       dv, H, N, rs.qkv, rs.o, nkb, (int)nblocks, scale * kLog2e, scale);
     const hipError_t e = hipGetLastError();
     return e == hipSuccess ? AVION_OK : hip_fail(e, "launch avion_dkdv_kernel");
 }
 
 // Kernel instances: four wavefronts per workgroup for every kernel and head size.
-template <int D>
-int fwd_dispatch(const bf16* q, const bf16* k, const bf16* v, bf16* o, float* lse, int B, int H, int N, float scale,
-                 hipStream_t st)
+int fwd_impl(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int N, int d, int packed,
+             float scale, void* stream)
 {
-    return launch_fwd<D, 4>(q, k, v, o, lse, B, H, N, scale, st);
-}
-
-template <int D>
-int dq_dispatch(const bf16* q, const bf16* k, const bf16* v, const bf16* o, const float* lse, const bf16* dO, bf16* dq,
-                float* rowsc, int B, int H, int N, float scale, hipStream_t st)
-{
-    return launch_dq<D, 4>(q, k, v, o, dO, lse, dq, rowsc, B, H, N, scale, st);
-}
-
-template <int D>
-int dkdv_dispatch(const bf16* q, const bf16* k, const bf16* v, const bf16* dO, bf16* dk, bf16* dv, const float* rowsc,
-                  int B, int H, int N, float scale, hipStream_t st)
-{
-    return launch_dkdv<D, 4>(q, k, v, dO, rowsc, dk, dv, B, H, N, scale, st);
+    if (!q || !k || !v || !o || !lse) return AVION_EINVAL;
+    const int rc = check_shape(B, H, N, d, scale, packed);
+    if (rc != AVION_OK) return rc;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(lse)) return AVION_EUNSUPPORTED;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const Strides rs{packed * H * d, H * d};
+    const bf16 *qq = static_cast<const bf16*>(q), *kk = static_cast<const bf16*>(k), *vv = static_cast<const bf16*>(v);
+    bf16* oo = static_cast<bf16*>(o);
+    if (d == 64) return launch_fwd<64, 4>(qq, kk, vv, oo, lse, B, H, N, rs, scale, st);
+    return launch_fwd<80, 4>(qq, kk, vv, oo, lse, B, H, N, rs, scale, st);
 }
 
 bool workspace_ok(const void* workspace, size_t workspace_bytes, int B, int H, int N, int d)
@@ -131,11 +131,64 @@ bool workspace_ok(const void* workspace, size_t workspace_bytes, int B, int H, i
            workspace_bytes >= avion_attn_bwd_workspace_bytes(B, H, N, d);
 }
 
+int dq_impl(const void* q, const void* k, const void* v, const void* o, const float* lse, const void* dO, void* dq, int B,
+            int H, int N, int d, int packed, float scale, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!q || !k || !v || !o || !lse || !dO || !dq) return AVION_EINVAL;
+    const int rc = check_shape(B, H, N, d, scale, packed);
+    if (rc != AVION_OK) return rc;
+    const void* ptrs[] = {q, k, v, o, lse, dO, dq};
+    for (const void* p : ptrs)
+        if (!aligned16(p)) return AVION_EUNSUPPORTED;
+    if (!workspace_ok(workspace, workspace_bytes, B, H, N, d)) return AVION_EWORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const Strides rs{packed * H * d, H * d};
+    float* rowsc = static_cast<float*>(workspace);  // receives LSE*log2e and -delta for the second pass
+    const bf16 *qq = static_cast<const bf16*>(q), *kk = static_cast<const bf16*>(k), *vv = static_cast<const bf16*>(v),
+               *oo = static_cast<const bf16*>(o), *gg = static_cast<const bf16*>(dO);
+    bf16* dqq = static_cast<bf16*>(dq);
+    if (d == 64) return launch_dq<64, 4>(qq, kk, vv, oo, gg, lse, dqq, rowsc, B, H, N, rs, scale, st);
+    return launch_dq<80, 4>(qq, kk, vv, oo, gg, lse, dqq, rowsc, B, H, N, rs, scale, st);
+}
+
+int dkdv_impl(const void* q, const void* k, const void* v, const float* lse, const void* dO, void* dk, void* dv, int B,
+              int H, int N, int d, int packed, float scale, const void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!q || !k || !v || !lse || !dO || !dk || !dv) return AVION_EINVAL;
+    const int rc = check_shape(B, H, N, d, scale, packed);
+    if (rc != AVION_OK) return rc;
+    const void* ptrs[] = {q, k, v, lse, dO, dk, dv};
+    for (const void* p : ptrs)
+        if (!aligned16(p)) return AVION_EUNSUPPORTED;
+    if (!workspace_ok(workspace, workspace_bytes, B, H, N, d)) return AVION_EWORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const Strides rs{packed * H * d, H * d};
+    const float* rowsc = static_cast<const float*>(workspace);  // LSE*log2e and -delta, left by the dQ pass
+    const bf16 *qq = static_cast<const bf16*>(q), *kk = static_cast<const bf16*>(k), *vv = static_cast<const bf16*>(v),
+               *gg = static_cast<const bf16*>(dO);
+    bf16 *dkk = static_cast<bf16*>(dk), *dvv = static_cast<bf16*>(dv);
+    if (d == 64) return launch_dkdv<64, 4>(qq, kk, vv, gg, rowsc, dkk, dvv, B, H, N, rs, scale, st);
+    return launch_dkdv<80, 4>(qq, kk, vv, gg, rowsc, dkk, dvv, B, H, N, rs, scale, st);
+}
+
+// q, k, v planes of a packed [B, N, 3, H, d] tensor
+struct Planes {
+    const char *q, *k, *v;
+    Planes(const void* qkv, int H, int d)
+    {
+        const char* p = static_cast<const char*>(qkv);
+        const size_t plane = (size_t)H * d * 2;
+        q = p;
+        k = p ? p + plane : nullptr;
+        v = p ? p + 2 * plane : nullptr;
+    }
+};
+
 }  // namespace
 
 extern "C" {
 
-int avion_version(void) { return 100; }
+int avion_version(void) { return 200; }
 
 const char* avion_strerror(int code)
 {
@@ -154,15 +207,14 @@ const char* avion_last_hip_error(void) { return g_hip_error; }
 int avion_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int N, int d,
                    float scale, void* stream)
 {
-    if (!q || !k || !v || !o || !lse) return AVION_EINVAL;
-    const int rc = check_shape(B, H, N, d, scale);
-    if (rc != AVION_OK) return rc;
-    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(lse)) return AVION_EUNSUPPORTED;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    const bf16 *qq = static_cast<const bf16*>(q), *kk = static_cast<const bf16*>(k), *vv = static_cast<const bf16*>(v);
-    bf16* oo = static_cast<bf16*>(o);
-    if (d == 64) return fwd_dispatch<64>(qq, kk, vv, oo, lse, B, H, N, scale, st);
-    return fwd_dispatch<80>(qq, kk, vv, oo, lse, B, H, N, scale, st);
+    return fwd_impl(q, k, v, o, lse, B, H, N, d, 1, scale, stream);
+}
+
+int avion_attn_fwd_qkvpacked(const void* qkv, void* o, float* lse, int B, int H, int N, int d, float scale, void* stream)
+{
+    if (H < 1 || d < 1) return AVION_EINVAL;
+    const Planes p(qkv, H, d);
+    return fwd_impl(p.q, p.k, p.v, o, lse, B, H, N, d, 3, scale, stream);
 }
 
 size_t avion_attn_bwd_workspace_bytes(int B, int H, int N, int d)
@@ -178,40 +230,14 @@ int avion_attn_bwd_dq(const void* q, const void* k, const void* v, const void* o
                       void* dq, int B, int H, int N, int d, float scale, void* workspace, size_t workspace_bytes,
                       void* stream)
 {
-    if (!q || !k || !v || !o || !lse || !dO || !dq) return AVION_EINVAL;
-    const int rc = check_shape(B, H, N, d, scale);
-    if (rc != AVION_OK) return rc;
-    const void* ptrs[] = {q, k, v, o, lse, dO, dq};
-    for (const void* p : ptrs)
-        if (!aligned16(p)) return AVION_EUNSUPPORTED;
-    if (!workspace_ok(workspace, workspace_bytes, B, H, N, d)) return AVION_EWORKSPACE;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    float* rowsc = static_cast<float*>(workspace);  // receives LSE*log2e and -delta for the second pass
-    const bf16 *qq = static_cast<const bf16*>(q), *kk = static_cast<const bf16*>(k), *vv = static_cast<const bf16*>(v),
-               *oo = static_cast<const bf16*>(o), *gg = static_cast<const bf16*>(dO);
-    bf16* dqq = static_cast<bf16*>(dq);
-    if (d == 64) return dq_dispatch<64>(qq, kk, vv, oo, lse, gg, dqq, rowsc, B, H, N, scale, st);
-    return dq_dispatch<80>(qq, kk, vv, oo, lse, gg, dqq, rowsc, B, H, N, scale, st);
+    return dq_impl(q, k, v, o, lse, dO, dq, B, H, N, d, 1, scale, workspace, workspace_bytes, stream);
 }
 
 int avion_attn_bwd_dkdv(const void* q, const void* k, const void* v, const float* lse, const void* dO, void* dk,
                         void* dv, int B, int H, int N, int d, float scale, const void* workspace,
                         size_t workspace_bytes, void* stream)
 {
-    if (!q || !k || !v || !lse || !dO || !dk || !dv) return AVION_EINVAL;
-    const int rc = check_shape(B, H, N, d, scale);
-    if (rc != AVION_OK) return rc;
-    const void* ptrs[] = {q, k, v, lse, dO, dk, dv};
-    for (const void* p : ptrs)
-        if (!aligned16(p)) return AVION_EUNSUPPORTED;
-    if (!workspace_ok(workspace, workspace_bytes, B, H, N, d)) return AVION_EWORKSPACE;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    const float* rowsc = static_cast<const float*>(workspace);  // LSE*log2e and -delta, left by the dQ pass
-    const bf16 *qq = static_cast<const bf16*>(q), *kk = static_cast<const bf16*>(k), *vv = static_cast<const bf16*>(v),
-               *gg = static_cast<const bf16*>(dO);
-    bf16 *dkk = static_cast<bf16*>(dk), *dvv = static_cast<bf16*>(dv);
-    if (d == 64) return dkdv_dispatch<64>(qq, kk, vv, gg, dkk, dvv, rowsc, B, H, N, scale, st);
-    return dkdv_dispatch<80>(qq, kk, vv, gg, dkk, dvv, rowsc, B, H, N, scale, st);
+    return dkdv_impl(q, k, v, lse, dO, dk, dv, B, H, N, d, 1, scale, workspace, workspace_bytes, stream);
 }
 
 int avion_attn_bwd(const void* q, const void* k, const void* v, const void* o, const float* lse, const void* dO,
@@ -226,9 +252,26 @@ int avion_attn_bwd(const void* q, const void* k, const void* v, const void* o, c
     for (const void* p : ptrs)
         if (!aligned16(p)) return AVION_EUNSUPPORTED;
     if (!workspace_ok(workspace, workspace_bytes, B, H, N, d)) return AVION_EWORKSPACE;
-    const int rq = avion_attn_bwd_dq(q, k, v, o, lse, dO, dq, B, H, N, d, scale, workspace, workspace_bytes, stream);
+    const int rq = dq_impl(q, k, v, o, lse, dO, dq, B, H, N, d, 1, scale, workspace, workspace_bytes, stream);
     if (rq != AVION_OK) return rq;
-    return avion_attn_bwd_dkdv(q, k, v, lse, dO, dk, dv, B, H, N, d, scale, workspace, workspace_bytes, stream);
+    return dkdv_impl(q, k, v, lse, dO, dk, dv, B, H, N, d, 1, scale, workspace, workspace_bytes, stream);
+}
+
+int avion_attn_bwd_qkvpacked(const void* qkv, const void* o, const float* lse, const void* dO, void* dqkv, int B, int H,
+                             int N, int d, float scale, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!qkv || !o || !lse || !dO || !dqkv) return AVION_EINVAL;
+    const int rc = check_shape(B, H, N, d, scale, 3);
+    if (rc != AVION_OK) return rc;
+    const void* ptrs[] = {qkv, o, lse, dO, dqkv};
+    for (const void* p : ptrs)
+        if (!aligned16(p)) return AVION_EUNSUPPORTED;
+    if (!workspace_ok(workspace, workspace_bytes, B, H, N, d)) return AVION_EWORKSPACE;
+    const Planes in(qkv, H, d), out(dqkv, H, d);
+    void *dq = const_cast<char*>(out.q), *dk = const_cast<char*>(out.k), *dv = const_cast<char*>(out.v);
+    const int rq = dq_impl(in.q, in.k, in.v, o, lse, dO, dq, B, H, N, d, 3, scale, workspace, workspace_bytes, stream);
+    if (rq != AVION_OK) return rq;
+    return dkdv_impl(in.q, in.k, in.v, lse, dO, dk, dv, B, H, N, d, 3, scale, workspace, workspace_bytes, stream);
 }
 
 }  // extern "C"

@@ -43,8 +43,8 @@ template <int D, int NW>
 __global__ void __launch_bounds__(NW * 64, (DqCfg<D, NW>::WAVES_PER_SIMD))
 avion_dq_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v,
                     const bf16* __restrict__ o, const bf16* __restrict__ dO, const float* __restrict__ lse,
-                    bf16* __restrict__ dq, float* __restrict__ rowsc, int H, int N, int nqb, int nblocks,
-                    float cs, float scale)
+                    bf16* __restrict__ dq, float* __restrict__ rowsc, int H, int N, int rs_qkv, int rs_o, int nqb,
+                    int nblocks, float cs, float scale)
 {
     using Cfg = DqCfg<D, NW>;
     using Ring = typename Cfg::Ring;
@@ -58,15 +58,16 @@ avion_dq_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf
     const int b = bh / H, h = bh % H;
     const int tid = threadIdx.x, lane = tid % 64, l32 = lane % 32, g = lane / 32;
     const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
-    const long rs = (long)H * D;
-    const long head_off = ((long)b * N * H + h) * D;
-    const SliceView kh(k + head_off, rs, N, D);
+    // token rows of Q, K, V, dQ are rs_qkv elements apart, those of O, dO rs_o
+    const long rs = rs_qkv;
+    const long head_off = (long)b * N * rs + (long)h * D;
+    const long head_off_o = (long)b * N * rs_o + (long)h * D;
     const int q0 = qb * BM + wave * 32;
     const bool wave_active = q0 < N;
     const int tr_off = tr_lane_offset(lane, STRIDE);
     const int ntiles = (N + BN - 1) / BN;
 
-    const Ring ring(k + head_off, v + head_off, kh.bytes, kh.row_bytes, nullptr, 0, ntiles, smem, wave, lane);
+    const Ring ring(k + head_off, rs, v + head_off, rs, N, nullptr, 0, ntiles, smem, wave, lane);
     ring.fetch(0);
 
     // Q and dO fragments (B operands), delta and LSE per lane
@@ -75,12 +76,13 @@ avion_dq_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf
     {
         const int row = min(q0 + l32, N - 1);
         const long off = head_off + (long)row * rs + g * 8;
+        const long off_o = head_off_o + (long)row * rs_o + g * 8;
         float part = 0.f;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             qf[ks] = *reinterpret_cast<const bf16x8*>(q + off + ks * 16);
-            gf[ks] = *reinterpret_cast<const bf16x8*>(dO + off + ks * 16);
-            const bf16x8 of = *reinterpret_cast<const bf16x8*>(o + off + ks * 16);
+            gf[ks] = *reinterpret_cast<const bf16x8*>(dO + off_o + ks * 16);
+            const bf16x8 of = *reinterpret_cast<const bf16x8*>(o + off_o + ks * 16);
 #pragma unroll
             for (int e = 0; e < 8; ++e) part = fmaf((float)of[e], (float)gf[ks][e], part);
         }
@@ -168,7 +170,8 @@ template <int D, int NW>
 __global__ void __launch_bounds__(NW * 64, (DkvCfg<D, NW>::WAVES_PER_SIMD))
 avion_dkdv_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v,
                       const bf16* __restrict__ dO, const float* __restrict__ rowsc, bf16* __restrict__ dk,
-                      bf16* __restrict__ dv, int H, int N, int nkb, int nblocks, float cs, float scale)
+                      bf16* __restrict__ dv, int H, int N, int rs_qkv, int rs_o, int nkb, int nblocks, float cs,
+                      float scale)
 {
     using Cfg = DkvCfg<D, NW>;
     using Ring = typename Cfg::Ring;
@@ -183,17 +186,18 @@ avion_dkdv_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const 
     const int b = bh / H, h = bh % H;
     const int tid = threadIdx.x, lane = tid % 64, l32 = lane % 32, g = lane / 32;
     const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
-    const long rs = (long)H * D;
-    const long head_off = ((long)b * N * H + h) * D;
-    const SliceView qh(q + head_off, rs, N, D);
+    // token rows of Q, K, V, dK, dV are rs_qkv elements apart, those of dO rs_o
+    const long rs = rs_qkv;
+    const long head_off = (long)b * N * rs + (long)h * D;
+    const long head_off_o = (long)b * N * rs_o + (long)h * D;
     const int npad = (N + 63) & ~63;
     const int ntiles = (N + BQ - 1) / BQ;
     const int k0 = kb * BNK + wave * 32;  // first key of this wavefront
     const bool wave_active = k0 < N;
     const int tr_off = tr_lane_offset(lane, STRIDE);
 
-    const Ring ring(q + head_off, dO + head_off, qh.bytes, qh.row_bytes, rowsc + (long)bh * 2 * npad, npad, ntiles, smem,
-                    wave, lane);
+    const Ring ring(q + head_off, rs, dO + head_off_o, rs_o, N, rowsc + (long)bh * 2 * npad, npad, ntiles, smem, wave,
+                    lane);
     ring.fetch(0);
 
     // K and V fragments (B operands: lane = key) stay in registers

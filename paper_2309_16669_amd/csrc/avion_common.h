@@ -151,13 +151,14 @@ DEVINL float frag_sum(bf16x8 f, float acc)
 // buffer resource: loads whose byte offset lies beyond the last row return zeros in hardware, so
 // tiles that hang over the end of the sequence need no branches.
 // ---------------------------------------------------------------------------------------------
+DEVINL unsigned slice_bytes(long rs, int N, int D) { return (unsigned)(((long)(N - 1) * rs + D) * 2); }
 struct SliceView {
     __amdgpu_buffer_rsrc_t rsrc;
     unsigned row_bytes;  // rs * 2
     unsigned bytes;      // extent of the slice
     DEVINL SliceView(const bf16* base, long rs, int N, int D)
     {
-        bytes = (unsigned)(((long)(N - 1) * rs + D) * 2);
+        bytes = slice_bytes(rs, N, D);
         rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16*>(base), 0, (int)bytes, 0x00020000);
         row_bytes = (unsigned)(rs * 2);
     }
@@ -339,11 +340,13 @@ struct TileRing {
     unsigned vstep[NPW];  // what a step to the next tile adds to it
     u32x4 desc[NPW];      // descriptor of the array the block comes from
 
-    DEVINL TileRing(const bf16* a, const bf16* b, unsigned bytes, unsigned row_bytes, const float* scalars, int npad,
+    // a, b: first rows of the two [N, D] slices, whose rows are rs_a and rs_b elements apart
+    DEVINL TileRing(const bf16* a, long rs_a, const bf16* b, long rs_b, int N, const float* scalars, int npad,
                     int ntiles_, char* smem_, int wave_, int lane)
         : smem(smem_), smem_addr(lds_address(smem_)), ntiles(ntiles_), wave(wave_)
     {
-        const RawBuffer a_buf(a, bytes), b_buf(b, bytes), s_buf(scalars, SCALARS ? 2u * npad * 4u : 0u);
+        const RawBuffer a_buf(a, slice_bytes(rs_a, N, D)), b_buf(b, slice_bytes(rs_b, N, D)),
+            s_buf(scalars, SCALARS ? 2u * npad * 4u : 0u);
 #pragma unroll
         for (int j = 0; j < NPW; ++j) {
             const int blk = wave + NW * j;
@@ -354,6 +357,7 @@ struct TileRing {
                 voff[j] = lane < 16 ? (unsigned)lane * 16 : lane < 32 ? (unsigned)(npad * 4 + (lane - 16) * 16) : kOutOfRangeBase;
                 vstep[j] = ROWS * 4;
             } else {
+                const unsigned row_bytes = (unsigned)((kind == 0 ? rs_a : rs_b) * 2);
                 voff[j] = padded_block_voff<D>(blk - kind * NTI, lane, row_bytes);
                 vstep[j] = ROWS * row_bytes;
             }

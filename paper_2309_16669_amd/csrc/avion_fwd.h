@@ -137,7 +137,8 @@ DEVINL void avion_fwd_safe_pass(char* smem, const SliceView& kh, const SliceView
 template <int D, int NW>
 __global__ void __launch_bounds__(NW * 64, (FwdCfg<D, NW>::WAVES_PER_SIMD))
 avion_fwd_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v,
-                 bf16* __restrict__ o, float* __restrict__ lse, int H, int N, int nqb, int nblocks, float cs)
+                 bf16* __restrict__ o, float* __restrict__ lse, int H, int N, int rs_qkv, int rs_o, int nqb, int nblocks,
+                 float cs)
 {
     using Cfg = FwdCfg<D, NW>;
     using Ring = typename Cfg::Ring;
@@ -152,8 +153,10 @@ avion_fwd_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const b
     const int b = bh / H, h = bh % H;
     const int tid = threadIdx.x, lane = tid % 64, l32 = lane % 32, g = lane / 32;
     const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
-    const long rs = (long)H * D;
-    const long head_off = ((long)b * N * H + h) * D;
+    // token rows of Q, K, V are rs_qkv elements apart, those of O rs_o; a batch entry is N such rows
+    const long rs = rs_qkv;
+    const long head_off = (long)b * N * rs + (long)h * D;
+    const long head_off_o = (long)b * N * rs_o + (long)h * D;
     const SliceView kh(k + head_off, rs, N, D);
     const SliceView vh(v + head_off, rs, N, D);
     const int q0 = qb * BM + wave * 32;  // first query of this wavefront
@@ -161,7 +164,7 @@ avion_fwd_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const b
     const int tr_off = tr_lane_offset(lane, STRIDE);
     const int ntiles = (N + BN - 1) / BN;
 
-    const Ring ring(k + head_off, v + head_off, kh.bytes, kh.row_bytes, nullptr, 0, ntiles, smem, wave, lane);
+    const Ring ring(k + head_off, rs, v + head_off, rs, N, nullptr, 0, ntiles, smem, wave, lane);
     ring.fetch(0);
 
     // Q fragments stay in registers for the whole kernel
@@ -250,6 +253,6 @@ avion_fwd_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const b
     for (int ct = 0; ct < CT; ++ct)
 #pragma unroll
         for (int i = 0; i < 16; ++i) oacc[ct][i] *= inv;
-    RowStore<D>::run(smem + wave * RowStore<D>::BYTES, oacc, 1.0f, o + head_off + (long)q0 * rs, rs, N - q0, lane);
+    RowStore<D>::run(smem + wave * RowStore<D>::BYTES, oacc, 1.0f, o + head_off_o + (long)q0 * rs_o, rs_o, N - q0, lane);
     if (g == 0 && q0 + l32 < N) lse[(long)bh * N + q0 + l32] = (m_used + __builtin_amdgcn_logf(l)) * kLn2;
 }

@@ -42,6 +42,25 @@ def run_hip(w, x, poison=True):
     return dict(o=o, lse=lse, dq=dq, dk=dk, dv=dv)
 
 
+def run_hip_packed(w, x, poison=True):
+    """The same through the packed-QKV entry points: q, k, v are interleaved into one [B,N,3,H,d]
+    tensor on the host (plain data movement), the gradients come back in that packing and are
+    returned as the three planes."""
+    import torch
+    import paper_2309_16669_amd as av
+    qkv = to_gpu_bf16(np.stack([x["q"], x["k"], x["v"]], axis=2))
+    dO = to_gpu_bf16(x["dO"])
+    fill = float("nan") if poison else 0.0
+    o = torch.full_like(dO, fill)
+    lse = torch.full((w.B, w.H, w.N), fill, dtype=torch.float32, device="cuda")
+    dqkv = torch.full_like(qkv, fill)
+    ws = torch.empty(av.attn_bwd_workspace_bytes(w.B, w.H, w.N, w.d), dtype=torch.uint8, device="cuda")
+    av.attn_fwd_qkvpacked(qkv, o, lse, w.scale)
+    av.attn_bwd_qkvpacked(qkv, o, lse, dO, dqkv, w.scale, ws)
+    torch.cuda.synchronize()
+    return dict(o=o, lse=lse, dq=dqkv[:, :, 0], dk=dqkv[:, :, 1], dv=dqkv[:, :, 2])
+
+
 def errors(gpu_f64, ref):
     diff = gpu_f64 - ref
     max_abs = float(np.abs(diff).max()) if diff.size else 0.0

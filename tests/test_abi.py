@@ -26,7 +26,8 @@ def test_library_exports_every_declared_symbol():
     lib = av.load_library()
     names = declared_symbols()
     assert {"avion_attn_fwd", "avion_attn_bwd", "avion_attn_bwd_workspace_bytes", "avion_strerror",
-            "avion_version", "avion_last_hip_error"} <= set(names)
+            "avion_version", "avion_last_hip_error", "avion_attn_fwd_qkvpacked",
+            "avion_attn_bwd_qkvpacked"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
     assert av.version() >= 100
@@ -90,6 +91,30 @@ def test_bwd_rejects_bad_arguments_without_launching(kwargs, code):
                             a["B"], a["H"], a["N"], a["d"], ctypes.c_float(a["scale"]),
                             a["ws"], a["ws_bytes"], None)
     assert rc == code
+
+
+@pytest.mark.parametrize("kwargs,code", [
+    (dict(qkv=0), av.EINVAL),
+    (dict(dqkv=0), av.EINVAL),
+    (dict(H=0), av.EINVAL),
+    (dict(d=96), av.EUNSUPPORTED),
+    (dict(qkv=FAKE + 8), av.EUNSUPPORTED),
+    (dict(ws_bytes=100), av.EWORKSPACE),
+    # a (batch, head) slice of the packed tensor must stay below 2^31 bytes: 3*H*d*2 bytes per token
+    (dict(H=64, N=100000), av.EUNSUPPORTED),
+])
+def test_packed_entry_points_reject_bad_arguments_without_launching(kwargs, code):
+    lib = av.load_library()
+    a = dict(qkv=FAKE, o=FAKE, lse=FAKE, dO=FAKE, dqkv=FAKE, B=1, H=2, N=64, d=64, scale=0.125, ws=FAKE,
+             ws_bytes=1 << 30)
+    a.update(kwargs)
+    rc = lib.avion_attn_bwd_qkvpacked(a["qkv"], a["o"], a["lse"], a["dO"], a["dqkv"], a["B"], a["H"], a["N"], a["d"],
+                                      ctypes.c_float(a["scale"]), a["ws"], a["ws_bytes"], None)
+    assert rc == code
+    if "dqkv" not in kwargs and "ws_bytes" not in kwargs:
+        rc = lib.avion_attn_fwd_qkvpacked(a["qkv"], a["o"], a["lse"], a["B"], a["H"], a["N"], a["d"],
+                                          ctypes.c_float(a["scale"]), None)
+        assert rc == code
 
 
 def test_binding_does_not_import_the_oracle():

@@ -84,6 +84,36 @@ def test_bitwise_reproducible(shape):
                                b[n].view(torch.int16) if b[n].dtype == torch.bfloat16 else b[n]), n
 
 
+@pytest.mark.parametrize("B,H,N,d", [(1, 1, 1, 64), (2, 3, 197, 64), (1, 2, 785, 64), (2, 2, 300, 80), (1, 12, 1569, 64)])
+def test_packed_qkv_entry_points(B, H, N, d):
+    # the [B,N,3,H,d] output of the joint projection taken as it is: against the oracle, and bit for
+    # bit against the unpacked entry points (the same kernels with another token stride)
+    import torch
+    w = si.small_workload(B, H, N, d, seed=500 + N + d)
+    x = si.make_inputs(w)
+    out = gh.run_hip_packed(w, x)
+    gh.check_against_oracle(w, x, out)
+    ref = gh.run_hip(w, x)
+    for n in ("o", "dq", "dk", "dv"):
+        assert torch.equal(out[n].contiguous().view(torch.int16), ref[n].view(torch.int16)), n
+    assert torch.equal(out["lse"], ref["lse"])
+
+
+def test_packed_qkv_at_the_benchmark_shape_on_sampled_heads():
+    w = si.WORKLOADS["vitb_batch"]
+    x = si.make_inputs(w)
+    out = gh.run_hip_packed(w, x)
+    gh.check_against_oracle(w, x, out, [(0, 0), (w.B - 1, w.H - 1), (w.B // 2, 5)])
+    import torch
+    for n in ("o", "dq", "dk", "dv", "lse"):
+        assert bool(torch.isfinite(out[n].float()).all()), n
+
+
+def test_longest_cls_token_shape():
+    # N = 3136 + 1: the 16-frame token count with a CLS token in front
+    _run(si.small_workload(1, 2, 3137, 64, seed=3137, scale=0.125))
+
+
 def test_identical_keys_and_single_token_closed_forms_on_gpu():
     # closed forms again, this time on the HIP path: identical keys -> O = mean of V
     import torch
