@@ -86,6 +86,9 @@ def main():
                     help="recipe = the synthetic N(0,1) inputs the metric is quoted on; zeros / ones = constant "
                          "operands, same instruction stream and traffic, to show how much of the time is the "
                          "data-dependent clock throttling of the chip (never the reported configuration)")
+    ap.add_argument("--dtype", choices=("bf16", "f16"), default="bf16",
+                    help="bf16 = the reported configuration; f16 = the fp16 entry points on the same draws "
+                         "rounded to fp16 (the CPU baseline is skipped: it would time the same oracle)")
     ap.add_argument("--layout", choices=("separate", "packed"), default="separate",
                     help="separate = q, k, v as three [B,N,H,d] tensors (the reported configuration); packed = one "
                          "[B,N,3,H,d] tensor through the *_qkvpacked entry points (same kernels, token stride 3*H*d)")
@@ -110,12 +113,17 @@ def main():
 
     w = si.WORKLOADS[args.workload]
     log(f"[bench] generating {w.name} {w.shape} ...")
-    x = si.make_inputs(w)
+    f16 = args.dtype == "f16"
+    if f16 and args.layout == "packed":
+        sys.exit("bench.py: the packed entry points exist for bf16 only")
+    x = si.make_inputs(w, fmt=args.dtype)
     dev = torch.device("cuda:0")
+    attn_fwd, attn_bwd = (av.attn_fwd_f16, av.attn_bwd_f16) if f16 else (av.attn_fwd, av.attn_bwd)
 
     def up(bits):
         import numpy as np
-        return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(dev).view(torch.bfloat16)
+        return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(dev).view(
+            torch.float16 if f16 else torch.bfloat16)
 
     q, k, v, dO = (up(x[n]) for n in ("q", "k", "v", "dO"))
     if args.operands != "recipe":
@@ -135,16 +143,21 @@ def main():
         log(f"[bench] calibration copy: {q.numel() * 2} bytes read, {q.numel() * 2} bytes written per launch")
 
     def fwd():
-        av.attn_fwd(q, k, v, o, lse, w.scale, stream)
+        attn_fwd(q, k, v, o, lse, w.scale, stream)
 
     def bwd():
-        av.attn_bwd(q, k, v, o, lse, dO, dq, dk, dv, w.scale, ws, stream)
+        attn_bwd(q, k, v, o, lse, dO, dq, dk, dv, w.scale, ws, stream)
+
+    # the phase entry points exist for bf16; for the phase split of an fp16 run they are fed the same
+    # bytes viewed as bf16 (same instruction stream and traffic, values irrelevant to a timing)
+    as_bf16 = (lambda t: t.view(torch.bfloat16)) if f16 else (lambda t: t)
 
     def bwd_dq():
-        av.attn_bwd_dq(q, k, v, o, lse, dO, dq, w.scale, ws, stream)
+        av.attn_bwd_dq(as_bf16(q), as_bf16(k), as_bf16(v), as_bf16(o), lse, as_bf16(dO), as_bf16(dq), w.scale, ws, stream)
 
     def bwd_dkdv():
-        av.attn_bwd_dkdv(q, k, v, lse, dO, dk, dv, w.scale, ws, stream)
+        av.attn_bwd_dkdv(as_bf16(q), as_bf16(k), as_bf16(v), lse, as_bf16(dO), as_bf16(dk), as_bf16(dv), w.scale, ws,
+                         stream)
 
     packed = args.layout == "packed"
     if packed:
@@ -174,9 +187,9 @@ def main():
     # per-phase times with HIP events on the launch stream
     ms_fwd = timed(fwd, args.steps, 2, stream)
     ms_bwd = timed(bwd, args.steps, 2, stream)
-    if packed:
-        # the packed call has no separate phases: split its time in the proportion of the two kernels
-        # on the separate layout (same kernels)
+    if packed or f16:
+        # these calls have no separate phases: split the backward's time in the proportion of the two
+        # kernels of the reported configuration
         a, b = timed(bwd_dq, args.steps, 2, stream), timed(bwd_dkdv, args.steps, 2, stream)
         ms_dq, ms_dkdv = ms_bwd * a / (a + b), ms_bwd * b / (a + b)
     else:
@@ -199,9 +212,9 @@ def main():
         "metric": "attention fwd+bwd TFLOP/s (N=1568,d=64) and % of MI355X bf16 MFMA peak",
         "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic" if args.operands == "recipe" else f"constant operands ({args.operands}), diagnostic only",
+        "dtype": args.dtype, "data": "synthetic" if args.operands == "recipe" else f"constant operands ({args.operands}), diagnostic only",
         "config": {"workload": f"{w.name}: B={w.B} H={w.H} N={w.N} d={w.d} non-causal, scale={w.scale:g}, "
-                               "Q/K/V/dO ~ N(0,1) bf16, fwd+bwd" + (", packed [B,N,3,H,d] QKV" if packed else "")},
+                               f"Q/K/V/dO ~ N(0,1) {args.dtype}, fwd+bwd" + (", packed [B,N,3,H,d] QKV" if packed else "")},
         "pct_of_bf16_mfma_peak": 100.0 * value / PEAK_BF16_TFLOPS,
         "phases": {
             "fwd": {"ms": ms_fwd, "tflops": tf(4 * base, ms_fwd), "pct_peak": 100 * tf(4 * base, ms_fwd) / PEAK_BF16_TFLOPS},
@@ -214,7 +227,7 @@ def main():
                      "algorithmic_flops_per_launch": dom_flops, "avg_launch_ms": dom_ms},
     }
     out["roofline"]["traffic"] = MEASURED_HBM_BYTES_PER_LAUNCH.get((args.workload, dom_name))
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not f16:
         log(f"[bench] timing the CPU oracle on {args.cpu_clips} clips ...")
         out["cpu_baseline"] = cpu_baseline(w, x, min(args.cpu_clips, w.B))
     print(json.dumps(out), flush=True)

@@ -133,6 +133,26 @@ int avion_attn_bwd_qkvpacked(const void *qkv, const void *o, const float *lse, c
                              void *dqkv, int B, int H, int N, int d, float scale,
                              void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * fp16 variants: the same operation on IEEE half-precision tensors, the type the paper's
+ * throughput and maximum-batch-size figure was measured in (its caption names torch.float16; the
+ * training setup in the implementation details uses automatic mixed precision).  Every tensor that is bf16 above is
+ * fp16 here (q, k, v, o, dO, dq, dk, dv); lse and the workspace are unchanged.  Same kernels with
+ * the fp16 MFMA; P and dS are rounded to fp16 before they enter a contraction, outputs once at the
+ * final store; accumulation and statistics stay fp32.  fp16 has 5 exponent bits: the caller's
+ * values must be representable (|x| <= 65504, gradients not below ~6e-8 in magnitude unless loss
+ * scaling has lifted them), as with any fp16 attention; inside the kernels the softmax weights
+ * are kept below 2^15 (a row that would exceed it takes the running-maximum path), P <= 1 in the
+ * backward pass.
+ */
+int avion_attn_fwd_f16(const void *q, const void *k, const void *v, void *o, float *lse,
+                       int B, int H, int N, int d, float scale, void *stream);
+
+int avion_attn_bwd_f16(const void *q, const void *k, const void *v, const void *o, const float *lse,
+                       const void *dO, void *dq, void *dk, void *dv,
+                       int B, int H, int N, int d, float scale,
+                       void *workspace, size_t workspace_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -55,6 +55,10 @@ def load_library() -> ctypes.CDLL:
         lib.avion_attn_fwd_qkvpacked.argtypes = [p, p, p, i, i, i, i, f, p]
         lib.avion_attn_bwd_qkvpacked.restype = i
         lib.avion_attn_bwd_qkvpacked.argtypes = [p, p, p, p, p, i, i, i, i, f, p, sz, p]
+        lib.avion_attn_fwd_f16.restype = i
+        lib.avion_attn_fwd_f16.argtypes = lib.avion_attn_fwd.argtypes
+        lib.avion_attn_bwd_f16.restype = i
+        lib.avion_attn_bwd_f16.argtypes = lib.avion_attn_bwd.argtypes
         _lib = lib
     return _lib
 
@@ -101,29 +105,49 @@ def attn_bwd_workspace_bytes(B: int, H: int, N: int, d: int) -> int:
     return int(load_library().avion_attn_bwd_workspace_bytes(B, H, N, d))
 
 
-def attn_fwd(q, k, v, o, lse, scale: float, stream=None) -> None:
-    """avion_attn_fwd on torch tensors: q,k,v,o bf16 [B,N,H,d] on the GPU; lse fp32 [B,H,N]."""
+def _fwd(entry, dt, q, k, v, o, lse, scale, stream):
     import torch
     B, N, H, d = q.shape
     for t, n in ((q, "q"), (k, "k"), (v, "v"), (o, "o")):
-        _require(t, n, torch.bfloat16, (B, N, H, d))
+        _require(t, n, dt, (B, N, H, d))
     _require(lse, "lse", torch.float32, (B, H, N))
-    _check(load_library().avion_attn_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), B, H, N, d,
-                                         float(scale), _stream_handle(stream)))
+    _check(entry(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), B, H, N, d, float(scale), _stream_handle(stream)))
+
+
+def _bwd(entry, dt, q, k, v, o, lse, dO, dq, dk, dv, scale, workspace, stream):
+    import torch
+    B, N, H, d = q.shape
+    for t, n in ((q, "q"), (k, "k"), (v, "v"), (o, "o"), (dO, "dO"), (dq, "dq"), (dk, "dk"), (dv, "dv")):
+        _require(t, n, dt, (B, N, H, d))
+    _require(lse, "lse", torch.float32, (B, H, N))
+    _require(workspace, "workspace", torch.uint8)
+    _check(entry(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(dO), _ptr(dq), _ptr(dk), _ptr(dv), B, H, N, d,
+                 float(scale), _ptr(workspace), workspace.numel(), _stream_handle(stream)))
+
+
+def attn_fwd(q, k, v, o, lse, scale: float, stream=None) -> None:
+    """avion_attn_fwd on torch tensors: q,k,v,o bf16 [B,N,H,d] on the GPU; lse fp32 [B,H,N]."""
+    import torch
+    _fwd(load_library().avion_attn_fwd, torch.bfloat16, q, k, v, o, lse, scale, stream)
+
+
+def attn_fwd_f16(q, k, v, o, lse, scale: float, stream=None) -> None:
+    """avion_attn_fwd_f16: the same on fp16 tensors."""
+    import torch
+    _fwd(load_library().avion_attn_fwd_f16, torch.float16, q, k, v, o, lse, scale, stream)
 
 
 def attn_bwd(q, k, v, o, lse, dO, dq, dk, dv, scale: float, workspace, stream=None) -> None:
     """avion_attn_bwd on torch tensors; `workspace` is a uint8 GPU tensor of at least
     attn_bwd_workspace_bytes(B,H,N,d) bytes."""
     import torch
-    B, N, H, d = q.shape
-    for t, n in ((q, "q"), (k, "k"), (v, "v"), (o, "o"), (dO, "dO"), (dq, "dq"), (dk, "dk"), (dv, "dv")):
-        _require(t, n, torch.bfloat16, (B, N, H, d))
-    _require(lse, "lse", torch.float32, (B, H, N))
-    _require(workspace, "workspace", torch.uint8)
-    _check(load_library().avion_attn_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(dO),
-                                         _ptr(dq), _ptr(dk), _ptr(dv), B, H, N, d, float(scale),
-                                         _ptr(workspace), workspace.numel(), _stream_handle(stream)))
+    _bwd(load_library().avion_attn_bwd, torch.bfloat16, q, k, v, o, lse, dO, dq, dk, dv, scale, workspace, stream)
+
+
+def attn_bwd_f16(q, k, v, o, lse, dO, dq, dk, dv, scale: float, workspace, stream=None) -> None:
+    """avion_attn_bwd_f16: the same on fp16 tensors."""
+    import torch
+    _bwd(load_library().avion_attn_bwd_f16, torch.float16, q, k, v, o, lse, dO, dq, dk, dv, scale, workspace, stream)
 
 
 def attn_bwd_dq(q, k, v, o, lse, dO, dq, scale: float, workspace, stream=None) -> None:

@@ -58,52 +58,52 @@ hipError_t allow_lds(K kernel, int bytes)
     return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
 }
 
-template <int D, int NW>
-int launch_fwd(const bf16* q, const bf16* k, const bf16* v, bf16* o, float* lse, int B, int H, int N, Strides rs,
+template <int D, int NW, typename E>
+int launch_fwd(const raw16* q, const raw16* k, const raw16* v, raw16* o, float* lse, int B, int H, int N, Strides rs,
                float scale, hipStream_t st)
 {
     using Cfg = FwdCfg<D, NW>;
-    static hipError_t attr = allow_lds(avion_fwd_kernel<D, NW>, Cfg::LDS_BYTES);
+    static hipError_t attr = allow_lds(avion_fwd_kernel<D, NW, E>, Cfg::LDS_BYTES);
     if (attr != hipSuccess) return hip_fail(attr, "hipFuncSetAttribute(fwd)");
     const int nqb = (N + Cfg::BM - 1) / Cfg::BM;
     const long long nblocks = (long long)nqb * B * H;
     unsigned grid;
     if (!grid_for(nblocks, &grid)) return AVION_EUNSUPPORTED;
-    hipLaunchKernelGGL((avion_fwd_kernel<D, NW>), dim3(grid), dim3(Cfg::NT), Cfg::LDS_BYTES, st, q, k, v, o, lse, H, N, rs.qkv,
+    hipLaunchKernelGGL((avion_fwd_kernel<D, NW, E>), dim3(grid), dim3(Cfg::NT), Cfg::LDS_BYTES, st, q, k, v, o, lse, H, N, rs.qkv,
                        rs.o, nqb, (int)nblocks, scale * kLog2e);
     const hipError_t e = hipGetLastError();
     return e == hipSuccess ? AVION_OK : hip_fail(e, "launch avion_fwd_kernel");
 }
 
-template <int D, int NW>
-int launch_dq(const bf16* q, const bf16* k, const bf16* v, const bf16* o, const bf16* dO, const float* lse, bf16* dq,
+template <int D, int NW, typename E>
+int launch_dq(const raw16* q, const raw16* k, const raw16* v, const raw16* o, const raw16* dO, const float* lse, raw16* dq,
               float* rowsc, int B, int H, int N, Strides rs, float scale, hipStream_t st)
 {
     using Cfg = DqCfg<D, NW>;
-    static hipError_t attr = allow_lds(avion_dq_kernel<D, NW>, Cfg::LDS_BYTES);
+    static hipError_t attr = allow_lds(avion_dq_kernel<D, NW, E>, Cfg::LDS_BYTES);
     if (attr != hipSuccess) return hip_fail(attr, "hipFuncSetAttribute(dq)");
     const int nqb = (N + Cfg::BM - 1) / Cfg::BM;
     const long long nblocks = (long long)nqb * B * H;
     unsigned grid;
     if (!grid_for(nblocks, &grid)) return AVION_EUNSUPPORTED;
-    hipLaunchKernelGGL((avion_dq_kernel<D, NW>), dim3(grid), dim3(Cfg::NT), Cfg::LDS_BYTES, st, q, k, v, o, dO, lse, dq,
+    hipLaunchKernelGGL((avion_dq_kernel<D, NW, E>), dim3(grid), dim3(Cfg::NT), Cfg::LDS_BYTES, st, q, k, v, o, dO, lse, dq,
                        rowsc, H, N, rs.qkv, rs.o, nqb, (int)nblocks, scale * kLog2e, scale);
     const hipError_t e = hipGetLastError();
     return e == hipSuccess ? AVION_OK : hip_fail(e, "launch avion_dq_kernel");
 }
 
-template <int D, int NW>
-int launch_dkdv(const bf16* q, const bf16* k, const bf16* v, const bf16* dO, const float* rowsc, bf16* dk, bf16* dv,
+template <int D, int NW, typename E>
+int launch_dkdv(const raw16* q, const raw16* k, const raw16* v, const raw16* dO, const float* rowsc, raw16* dk, raw16* dv,
                 int B, int H, int N, Strides rs, float scale, hipStream_t st)
 {
     using Cfg = DkvCfg<D, NW>;
-    static hipError_t attr = allow_lds(avion_dkdv_kernel<D, NW>, Cfg::LDS_BYTES);
+    static hipError_t attr = allow_lds(avion_dkdv_kernel<D, NW, E>, Cfg::LDS_BYTES);
     if (attr != hipSuccess) return hip_fail(attr, "hipFuncSetAttribute(dkdv)");
     const int nkb = (N + Cfg::BNK - 1) / Cfg::BNK;
     const long long nblocks = (long long)nkb * B * H;
     unsigned grid;
     if (!grid_for(nblocks, &grid)) return AVION_EUNSUPPORTED;
-    hipLaunchKernelGGL((avion_dkdv_kernel<D, NW>), dim3(grid), dim3(Cfg::NT), Cfg::LDS_BYTES, st, q, k, v, dO, rowsc, dk,
+    hipLaunchKernelGGL((avion_dkdv_kernel<D, NW, E>), dim3(grid), dim3(Cfg::NT), Cfg::LDS_BYTES, st, q, k, v, dO, rowsc, dk,
                        dv, H, N, rs.qkv, rs.o, nkb, (int)nblocks, scale * kLog2e, scale);
     const hipError_t e = hipGetLastError();
     return e == hipSuccess ? AVION_OK : hip_fail(e, "launch avion_dkdv_kernel");
@@ -111,7 +111,7 @@ int launch_dkdv(const bf16* q, const bf16* k, const bf16* v, const bf16* dO, con
 
 // Kernel instances: four wavefronts per workgroup for every kernel and head size.
 int fwd_impl(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int N, int d, int packed,
-             float scale, void* stream)
+             bool f16, float scale, void* stream)
 {
     if (!q || !k || !v || !o || !lse) return AVION_EINVAL;
     const int rc = check_shape(B, H, N, d, scale, packed);
@@ -119,10 +119,14 @@ int fwd_impl(const void* q, const void* k, const void* v, void* o, float* lse, i
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(lse)) return AVION_EUNSUPPORTED;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const Strides rs{packed * H * d, H * d};
-    const bf16 *qq = static_cast<const bf16*>(q), *kk = static_cast<const bf16*>(k), *vv = static_cast<const bf16*>(v);
-    bf16* oo = static_cast<bf16*>(o);
-    if (d == 64) return launch_fwd<64, 4>(qq, kk, vv, oo, lse, B, H, N, rs, scale, st);
-    return launch_fwd<80, 4>(qq, kk, vv, oo, lse, B, H, N, rs, scale, st);
+    const raw16 *qq = static_cast<const raw16*>(q), *kk = static_cast<const raw16*>(k), *vv = static_cast<const raw16*>(v);
+    raw16* oo = static_cast<raw16*>(o);
+    if (f16) {
+        if (d == 64) return launch_fwd<64, 4, F16>(qq, kk, vv, oo, lse, B, H, N, rs, scale, st);
+        return launch_fwd<80, 4, F16>(qq, kk, vv, oo, lse, B, H, N, rs, scale, st);
+    }
+    if (d == 64) return launch_fwd<64, 4, Bf16>(qq, kk, vv, oo, lse, B, H, N, rs, scale, st);
+    return launch_fwd<80, 4, Bf16>(qq, kk, vv, oo, lse, B, H, N, rs, scale, st);
 }
 
 bool workspace_ok(const void* workspace, size_t workspace_bytes, int B, int H, int N, int d)
@@ -132,7 +136,7 @@ bool workspace_ok(const void* workspace, size_t workspace_bytes, int B, int H, i
 }
 
 int dq_impl(const void* q, const void* k, const void* v, const void* o, const float* lse, const void* dO, void* dq, int B,
-            int H, int N, int d, int packed, float scale, void* workspace, size_t workspace_bytes, void* stream)
+            int H, int N, int d, int packed, bool f16, float scale, void* workspace, size_t workspace_bytes, void* stream)
 {
     if (!q || !k || !v || !o || !lse || !dO || !dq) return AVION_EINVAL;
     const int rc = check_shape(B, H, N, d, scale, packed);
@@ -144,15 +148,20 @@ int dq_impl(const void* q, const void* k, const void* v, const void* o, const fl
     hipStream_t st = static_cast<hipStream_t>(stream);
     const Strides rs{packed * H * d, H * d};
     float* rowsc = static_cast<float*>(workspace);  // receives LSE*log2e and -delta for the second pass
-    const bf16 *qq = static_cast<const bf16*>(q), *kk = static_cast<const bf16*>(k), *vv = static_cast<const bf16*>(v),
-               *oo = static_cast<const bf16*>(o), *gg = static_cast<const bf16*>(dO);
-    bf16* dqq = static_cast<bf16*>(dq);
-    if (d == 64) return launch_dq<64, 4>(qq, kk, vv, oo, gg, lse, dqq, rowsc, B, H, N, rs, scale, st);
-    return launch_dq<80, 4>(qq, kk, vv, oo, gg, lse, dqq, rowsc, B, H, N, rs, scale, st);
+    const raw16 *qq = static_cast<const raw16*>(q), *kk = static_cast<const raw16*>(k), *vv = static_cast<const raw16*>(v),
+               *oo = static_cast<const raw16*>(o), *gg = static_cast<const raw16*>(dO);
+    raw16* dqq = static_cast<raw16*>(dq);
+    if (f16) {
+        if (d == 64) return launch_dq<64, 4, F16>(qq, kk, vv, oo, gg, lse, dqq, rowsc, B, H, N, rs, scale, st);
+        return launch_dq<80, 4, F16>(qq, kk, vv, oo, gg, lse, dqq, rowsc, B, H, N, rs, scale, st);
+    }
+    if (d == 64) return launch_dq<64, 4, Bf16>(qq, kk, vv, oo, gg, lse, dqq, rowsc, B, H, N, rs, scale, st);
+    return launch_dq<80, 4, Bf16>(qq, kk, vv, oo, gg, lse, dqq, rowsc, B, H, N, rs, scale, st);
 }
 
 int dkdv_impl(const void* q, const void* k, const void* v, const float* lse, const void* dO, void* dk, void* dv, int B,
-              int H, int N, int d, int packed, float scale, const void* workspace, size_t workspace_bytes, void* stream)
+              int H, int N, int d, int packed, bool f16, float scale, const void* workspace, size_t workspace_bytes,
+              void* stream)
 {
     if (!q || !k || !v || !lse || !dO || !dk || !dv) return AVION_EINVAL;
     const int rc = check_shape(B, H, N, d, scale, packed);
@@ -164,11 +173,32 @@ int dkdv_impl(const void* q, const void* k, const void* v, const float* lse, con
     hipStream_t st = static_cast<hipStream_t>(stream);
     const Strides rs{packed * H * d, H * d};
     const float* rowsc = static_cast<const float*>(workspace);  // LSE*log2e and -delta, left by the dQ pass
-    const bf16 *qq = static_cast<const bf16*>(q), *kk = static_cast<const bf16*>(k), *vv = static_cast<const bf16*>(v),
-               *gg = static_cast<const bf16*>(dO);
-    bf16 *dkk = static_cast<bf16*>(dk), *dvv = static_cast<bf16*>(dv);
-    if (d == 64) return launch_dkdv<64, 4>(qq, kk, vv, gg, rowsc, dkk, dvv, B, H, N, rs, scale, st);
-    return launch_dkdv<80, 4>(qq, kk, vv, gg, rowsc, dkk, dvv, B, H, N, rs, scale, st);
+    const raw16 *qq = static_cast<const raw16*>(q), *kk = static_cast<const raw16*>(k), *vv = static_cast<const raw16*>(v),
+               *gg = static_cast<const raw16*>(dO);
+    raw16 *dkk = static_cast<raw16*>(dk), *dvv = static_cast<raw16*>(dv);
+    if (f16) {
+        if (d == 64) return launch_dkdv<64, 4, F16>(qq, kk, vv, gg, rowsc, dkk, dvv, B, H, N, rs, scale, st);
+        return launch_dkdv<80, 4, F16>(qq, kk, vv, gg, rowsc, dkk, dvv, B, H, N, rs, scale, st);
+    }
+    if (d == 64) return launch_dkdv<64, 4, Bf16>(qq, kk, vv, gg, rowsc, dkk, dvv, B, H, N, rs, scale, st);
+    return launch_dkdv<80, 4, Bf16>(qq, kk, vv, gg, rowsc, dkk, dvv, B, H, N, rs, scale, st);
+}
+
+int bwd_impl(const void* q, const void* k, const void* v, const void* o, const float* lse, const void* dO, void* dq,
+             void* dk, void* dv, int B, int H, int N, int d, bool f16, float scale, void* workspace, size_t workspace_bytes,
+             void* stream)
+{
+    // every argument is checked before the first launch, so an error leaves all outputs untouched
+    if (!q || !k || !v || !o || !lse || !dO || !dq || !dk || !dv) return AVION_EINVAL;
+    const int rc = check_shape(B, H, N, d, scale);
+    if (rc != AVION_OK) return rc;
+    const void* ptrs[] = {q, k, v, o, lse, dO, dq, dk, dv};
+    for (const void* p : ptrs)
+        if (!aligned16(p)) return AVION_EUNSUPPORTED;
+    if (!workspace_ok(workspace, workspace_bytes, B, H, N, d)) return AVION_EWORKSPACE;
+    const int rq = dq_impl(q, k, v, o, lse, dO, dq, B, H, N, d, 1, f16, scale, workspace, workspace_bytes, stream);
+    if (rq != AVION_OK) return rq;
+    return dkdv_impl(q, k, v, lse, dO, dk, dv, B, H, N, d, 1, f16, scale, workspace, workspace_bytes, stream);
 }
 
 // q, k, v planes of a packed [B, N, 3, H, d] tensor
@@ -207,14 +237,14 @@ const char* avion_last_hip_error(void) { return g_hip_error; }
 int avion_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int N, int d,
                    float scale, void* stream)
 {
-    return fwd_impl(q, k, v, o, lse, B, H, N, d, 1, scale, stream);
+    return fwd_impl(q, k, v, o, lse, B, H, N, d, 1, false, scale, stream);
 }
 
 int avion_attn_fwd_qkvpacked(const void* qkv, void* o, float* lse, int B, int H, int N, int d, float scale, void* stream)
 {
     if (H < 1 || d < 1) return AVION_EINVAL;
     const Planes p(qkv, H, d);
-    return fwd_impl(p.q, p.k, p.v, o, lse, B, H, N, d, 3, scale, stream);
+    return fwd_impl(p.q, p.k, p.v, o, lse, B, H, N, d, 3, false, scale, stream);
 }
 
 size_t avion_attn_bwd_workspace_bytes(int B, int H, int N, int d)
@@ -230,31 +260,34 @@ int avion_attn_bwd_dq(const void* q, const void* k, const void* v, const void* o
                       void* dq, int B, int H, int N, int d, float scale, void* workspace, size_t workspace_bytes,
                       void* stream)
 {
-    return dq_impl(q, k, v, o, lse, dO, dq, B, H, N, d, 1, scale, workspace, workspace_bytes, stream);
+    return dq_impl(q, k, v, o, lse, dO, dq, B, H, N, d, 1, false, scale, workspace, workspace_bytes, stream);
 }
 
 int avion_attn_bwd_dkdv(const void* q, const void* k, const void* v, const float* lse, const void* dO, void* dk,
                         void* dv, int B, int H, int N, int d, float scale, const void* workspace,
                         size_t workspace_bytes, void* stream)
 {
-    return dkdv_impl(q, k, v, lse, dO, dk, dv, B, H, N, d, 1, scale, workspace, workspace_bytes, stream);
+    return dkdv_impl(q, k, v, lse, dO, dk, dv, B, H, N, d, 1, false, scale, workspace, workspace_bytes, stream);
 }
 
 int avion_attn_bwd(const void* q, const void* k, const void* v, const void* o, const float* lse, const void* dO,
                    void* dq, void* dk, void* dv, int B, int H, int N, int d, float scale, void* workspace,
                    size_t workspace_bytes, void* stream)
 {
-    // every argument is checked before the first launch, so an error leaves all outputs untouched
-    if (!q || !k || !v || !o || !lse || !dO || !dq || !dk || !dv) return AVION_EINVAL;
-    const int rc = check_shape(B, H, N, d, scale);
-    if (rc != AVION_OK) return rc;
-    const void* ptrs[] = {q, k, v, o, lse, dO, dq, dk, dv};
-    for (const void* p : ptrs)
-        if (!aligned16(p)) return AVION_EUNSUPPORTED;
-    if (!workspace_ok(workspace, workspace_bytes, B, H, N, d)) return AVION_EWORKSPACE;
-    const int rq = dq_impl(q, k, v, o, lse, dO, dq, B, H, N, d, 1, scale, workspace, workspace_bytes, stream);
-    if (rq != AVION_OK) return rq;
-    return dkdv_impl(q, k, v, lse, dO, dk, dv, B, H, N, d, 1, scale, workspace, workspace_bytes, stream);
+    return bwd_impl(q, k, v, o, lse, dO, dq, dk, dv, B, H, N, d, false, scale, workspace, workspace_bytes, stream);
+}
+
+int avion_attn_fwd_f16(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int N, int d,
+                       float scale, void* stream)
+{
+    return fwd_impl(q, k, v, o, lse, B, H, N, d, 1, true, scale, stream);
+}
+
+int avion_attn_bwd_f16(const void* q, const void* k, const void* v, const void* o, const float* lse, const void* dO,
+                       void* dq, void* dk, void* dv, int B, int H, int N, int d, float scale, void* workspace,
+                       size_t workspace_bytes, void* stream)
+{
+    return bwd_impl(q, k, v, o, lse, dO, dq, dk, dv, B, H, N, d, true, scale, workspace, workspace_bytes, stream);
 }
 
 int avion_attn_bwd_qkvpacked(const void* qkv, const void* o, const float* lse, const void* dO, void* dqkv, int B, int H,
@@ -269,9 +302,10 @@ int avion_attn_bwd_qkvpacked(const void* qkv, const void* o, const float* lse, c
     if (!workspace_ok(workspace, workspace_bytes, B, H, N, d)) return AVION_EWORKSPACE;
     const Planes in(qkv, H, d), out(dqkv, H, d);
     void *dq = const_cast<char*>(out.q), *dk = const_cast<char*>(out.k), *dv = const_cast<char*>(out.v);
-    const int rq = dq_impl(in.q, in.k, in.v, o, lse, dO, dq, B, H, N, d, 3, scale, workspace, workspace_bytes, stream);
+    const int rq = dq_impl(in.q, in.k, in.v, o, lse, dO, dq, B, H, N, d, 3, false, scale, workspace, workspace_bytes,
+                           stream);
     if (rq != AVION_OK) return rq;
-    return dkdv_impl(in.q, in.k, in.v, lse, dO, dk, dv, B, H, N, d, 3, scale, workspace, workspace_bytes, stream);
+    return dkdv_impl(in.q, in.k, in.v, lse, dO, dk, dv, B, H, N, d, 3, false, scale, workspace, workspace_bytes, stream);
 }
 
 }  // extern "C"

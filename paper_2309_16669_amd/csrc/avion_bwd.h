@@ -39,11 +39,11 @@ struct DqCfg {
     static constexpr int WAVES_PER_SIMD = D == 64 ? 3 : 2;  // LDS would allow more; registers do not
 };
 
-template <int D, int NW>
+template <int D, int NW, typename E>
 __global__ void __launch_bounds__(NW * 64, (DqCfg<D, NW>::WAVES_PER_SIMD))
-avion_dq_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v,
-                    const bf16* __restrict__ o, const bf16* __restrict__ dO, const float* __restrict__ lse,
-                    bf16* __restrict__ dq, float* __restrict__ rowsc, int H, int N, int rs_qkv, int rs_o, int nqb,
+avion_dq_kernel(const raw16* __restrict__ q, const raw16* __restrict__ k, const raw16* __restrict__ v,
+                    const raw16* __restrict__ o, const raw16* __restrict__ dO, const float* __restrict__ lse,
+                    raw16* __restrict__ dq, float* __restrict__ rowsc, int H, int N, int rs_qkv, int rs_o, int nqb,
                     int nblocks, float cs, float scale)
 {
     using Cfg = DqCfg<D, NW>;
@@ -71,7 +71,7 @@ avion_dq_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf
     ring.fetch(0);
 
     // Q and dO fragments (B operands), delta and LSE per lane
-    bf16x8 qf[KS], gf[KS];
+    frag8 qf[KS], gf[KS];
     float lc, dl;
     {
         const int row = min(q0 + l32, N - 1);
@@ -80,11 +80,11 @@ avion_dq_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf
         float part = 0.f;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-            qf[ks] = *reinterpret_cast<const bf16x8*>(q + off + ks * 16);
-            gf[ks] = *reinterpret_cast<const bf16x8*>(dO + off_o + ks * 16);
-            const bf16x8 of = *reinterpret_cast<const bf16x8*>(o + off_o + ks * 16);
+            qf[ks] = *reinterpret_cast<const frag8*>(q + off + ks * 16);
+            gf[ks] = *reinterpret_cast<const frag8*>(dO + off_o + ks * 16);
+            const frag8 of = *reinterpret_cast<const frag8*>(o + off_o + ks * 16);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) part = fmaf((float)of[e], (float)gf[ks][e], part);
+            for (int e = 0; e < 8; ++e) part = fmaf(E::widen(of, e), E::widen(gf[ks], e), part);
         }
         dl = both_halves_sum(part);
         lc = lse[(long)bh * N + row] * kLog2e;
@@ -112,13 +112,13 @@ avion_dq_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf
         if constexpr (RAGGED) s = key_mask_block(key_base, g, N);
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-            const bf16x8 ak = nat_frag(kt, STRIDE, 32 * hk + l32, ks, g);
-            const bf16x8 av = nat_frag(vt, STRIDE, 32 * hk + l32, ks, g);
-            s = mfma32(ak, qf[ks], ks == 0 && !RAGGED ? f32x16_zero() : s);
-            dp = mfma32(av, gf[ks], ks == 0 ? f32x16_zero() : dp);
+            const frag8 ak = nat_frag(kt, STRIDE, 32 * hk + l32, ks, g);
+            const frag8 av = nat_frag(vt, STRIDE, 32 * hk + l32, ks, g);
+            s = E::mfma(ak, qf[ks], ks == 0 && !RAGGED ? f32x16_zero() : s);
+            dp = E::mfma(av, gf[ks], ks == 0 ? f32x16_zero() : dp);
         }
         // the K^T operands are requested before the vector work so that they are there after it
-        bf16x8 kt_f[2][CT];
+        frag8 kt_f[2][CT];
 #pragma unroll
         for (int half = 0; half < 2; ++half)
 #pragma unroll
@@ -128,12 +128,12 @@ avion_dq_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf
         for (int i = 0; i < 16; ++i) {
             const float pe = fast_exp2(fmaf(s[i], cs, nlc));
             s[i] = pe * (dp[i] - dl);
-            if (i % 2 == 1) df[i / 8][(i / 2) % 4] = pack_bf16(s[i - 1], s[i]);
+            if (i % 2 == 1) df[i / 8][(i / 2) % 4] = E::pack(s[i - 1], s[i]);
         }
 #pragma unroll
         for (int half = 0; half < 2; ++half)
 #pragma unroll
-            for (int ct = 0; ct < CT; ++ct) acc[ct] = mfma32(kt_f[half][ct], as_bf16x8(df[half]), acc[ct]);
+            for (int ct = 0; ct < CT; ++ct) acc[ct] = E::mfma(kt_f[half][ct], as_frag8(df[half]), acc[ct]);
     };
 
     for (int t = 0; t < ntiles; ++t) {
@@ -149,7 +149,7 @@ avion_dq_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf
         Ring::landed_barrier();  // tile t+1 has landed; tile t is no longer read
     }
     if (!wave_active) return;
-    RowStore<D>::run(smem + wave * RowStore<D>::BYTES, acc, scale, dq + head_off + (long)q0 * rs, rs, N - q0, lane);
+    RowStore<D, E>::run(smem + wave * RowStore<D, E>::BYTES, acc, scale, dq + head_off + (long)q0 * rs, rs, N - q0, lane);
 }
 
 // ------------------------------------------------------------------------------------------ dK, dV
@@ -166,11 +166,11 @@ struct DkvCfg {
     static constexpr int WAVES_PER_SIMD = 2;  // a floor for the register budget; D = 64 fits three
 };
 
-template <int D, int NW>
+template <int D, int NW, typename E>
 __global__ void __launch_bounds__(NW * 64, (DkvCfg<D, NW>::WAVES_PER_SIMD))
-avion_dkdv_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v,
-                      const bf16* __restrict__ dO, const float* __restrict__ rowsc, bf16* __restrict__ dk,
-                      bf16* __restrict__ dv, int H, int N, int rs_qkv, int rs_o, int nkb, int nblocks, float cs,
+avion_dkdv_kernel(const raw16* __restrict__ q, const raw16* __restrict__ k, const raw16* __restrict__ v,
+                      const raw16* __restrict__ dO, const float* __restrict__ rowsc, raw16* __restrict__ dk,
+                      raw16* __restrict__ dv, int H, int N, int rs_qkv, int rs_o, int nkb, int nblocks, float cs,
                       float scale)
 {
     using Cfg = DkvCfg<D, NW>;
@@ -201,14 +201,14 @@ avion_dkdv_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const 
     ring.fetch(0);
 
     // K and V fragments (B operands: lane = key) stay in registers
-    bf16x8 kf[KS], vf[KS];
+    frag8 kf[KS], vf[KS];
     {
         const int row = min(k0 + l32, N - 1);
         const long off = head_off + (long)row * rs + g * 8;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-            kf[ks] = *reinterpret_cast<const bf16x8*>(k + off + ks * 16);
-            vf[ks] = *reinterpret_cast<const bf16x8*>(v + off + ks * 16);
+            kf[ks] = *reinterpret_cast<const frag8*>(k + off + ks * 16);
+            vf[ks] = *reinterpret_cast<const frag8*>(v + off + ks * 16);
         }
     }
     f32x16 dka[CT], dva[CT];
@@ -236,10 +236,10 @@ avion_dkdv_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const 
                 }
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
-                    const bf16x8 aq = nat_frag(buf, STRIDE, 32 * hq + l32, ks, g);
-                    const bf16x8 ag = nat_frag(buf + OFF_G, STRIDE, 32 * hq + l32, ks, g);
-                    s = mfma32(aq, kf[ks], ks == 0 ? f32x16_zero() : s);
-                    dp = mfma32(ag, vf[ks], dp);
+                    const frag8 aq = nat_frag(buf, STRIDE, 32 * hq + l32, ks, g);
+                    const frag8 ag = nat_frag(buf + OFF_G, STRIDE, 32 * hq + l32, ks, g);
+                    s = E::mfma(aq, kf[ks], ks == 0 ? f32x16_zero() : s);
+                    dp = E::mfma(ag, vf[ks], dp);
                 }
                 f32x4 l4[4];
 #pragma unroll
@@ -247,7 +247,7 @@ avion_dkdv_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const 
                 // per query half (16 queries): transposed operands requested before the vector work
 #pragma unroll
                 for (int half = 0; half < 2; ++half) {
-                    bf16x8 tg[CT], tq[CT];
+                    frag8 tg[CT], tq[CT];
 #pragma unroll
                     for (int ct = 0; ct < CT; ++ct) {
                         tg[ct] = tr_frag(buf + OFF_G, STRIDE, tr_off, ct, 2 * hq + half);
@@ -260,14 +260,14 @@ avion_dkdv_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const 
                         s[e] = pe;
                         dp[e] = pe * dp[e];
                         if (e % 2 == 1) {
-                            pf[(e / 2) % 4] = pack_bf16(s[e - 1], s[e]);
-                            df[(e / 2) % 4] = pack_bf16(dp[e - 1], dp[e]);
+                            pf[(e / 2) % 4] = E::pack(s[e - 1], s[e]);
+                            df[(e / 2) % 4] = E::pack(dp[e - 1], dp[e]);
                         }
                     }
 #pragma unroll
                     for (int ct = 0; ct < CT; ++ct) {
-                        dva[ct] = mfma32(tg[ct], as_bf16x8(pf), dva[ct]);
-                        dka[ct] = mfma32(tq[ct], as_bf16x8(df), dka[ct]);
+                        dva[ct] = E::mfma(tg[ct], as_frag8(pf), dva[ct]);
+                        dka[ct] = E::mfma(tq[ct], as_frag8(df), dka[ct]);
                     }
                 }
             }
@@ -275,7 +275,7 @@ avion_dkdv_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const 
         Ring::landed_barrier();  // tile t+1 has landed; tile t is no longer read
     }
     if (!wave_active) return;
-    char* region = smem + wave * RowStore<D>::BYTES;
-    RowStore<D>::run(region, dka, scale, dk + head_off + (long)k0 * rs, rs, N - k0, lane);
-    RowStore<D>::run(region, dva, 1.0f, dv + head_off + (long)k0 * rs, rs, N - k0, lane);
+    char* region = smem + wave * RowStore<D, E>::BYTES;
+    RowStore<D, E>::run(region, dka, scale, dk + head_off + (long)k0 * rs, rs, N - k0, lane);
+    RowStore<D, E>::run(region, dva, 1.0f, dv + head_off + (long)k0 * rs, rs, N - k0, lane);
 }

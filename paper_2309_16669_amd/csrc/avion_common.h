@@ -2,7 +2,7 @@
 //
 // Register and LDS layouts used throughout
 // ----------------------------------------
-// All contractions use v_mfma_f32_32x32x16_bf16 (one wavefront, 32x32 output tile, 16 deep):
+// All contractions use v_mfma_f32_32x32x16_bf16 or _f16 (one wavefront, 32x32 output tile, 16 deep):
 //   A operand (32 x 16): lane l holds row  l%32, contraction slots 8*(l/32) .. 8*(l/32)+7
 //   B operand (16 x 32): lane l holds col  l%32, contraction slots 8*(l/32) .. 8*(l/32)+7
 //   accumulator (32x32): lane l holds col  l%32; register v (0..15) holds row
@@ -31,10 +31,9 @@
 
 #define DEVINL __device__ __forceinline__
 
-typedef __bf16 bf16;
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef unsigned short raw16;  // one tensor element of either format, as bits
+// 16 bytes = 8 elements: the unit every MFMA operand fragment is moved and held in
+typedef __attribute__((ext_vector_type(8))) short frag8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
@@ -46,18 +45,67 @@ typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
-DEVINL f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c)
-{
-    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
-}
-
 DEVINL f32x16 f32x16_zero()
 {
     const f32x16 z = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     return z;
 }
 
-DEVINL bf16x8 as_bf16x8(u32x4 x) { return __builtin_bit_cast(bf16x8, x); }
+DEVINL frag8 as_frag8(u32x4 x) { return __builtin_bit_cast(frag8, x); }
+
+// ---------------------------------------------------------------------------------------------
+// Element formats of the tensors.  Both are two bytes wide, so tiles, fragments and addressing are
+// the same; only the contraction instruction, the roundings (nearest even in both) and the
+// conversions differ.  kRowSumLimit is the forward pass's bound on a row sum of weights taken
+// against the fixed reference (see avion_fwd.h): every weight is at most the sum, so the bound also
+// keeps each weight representable in the format it is rounded to.
+// ---------------------------------------------------------------------------------------------
+struct Bf16 {
+    typedef __attribute__((ext_vector_type(8))) __bf16 v8;
+    typedef __attribute__((ext_vector_type(2))) __bf16 v2;
+    static constexpr float kRowSumLimit = 7.9e28f;  // 2^96; bf16 has the exponent range of fp32
+    DEVINL static f32x16 mfma(frag8 a, frag8 b, f32x16 c)
+    {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8, a), __builtin_bit_cast(v8, b), c, 0, 0, 0);
+    }
+    // two fp32 -> packed pair, low half = a
+    DEVINL static unsigned pack(float a, float b)
+    {
+        v2 p;
+        p[0] = (__bf16)a;
+        p[1] = (__bf16)b;
+        return __builtin_bit_cast(unsigned, p);
+    }
+    // acc + both elements of a packed pair (fp32 accumulation, v_dot2 with a vector of ones)
+    DEVINL static float add_pair(unsigned pair, float acc)
+    {
+        const v2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+        return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(v2, pair), ones, acc, false);
+    }
+    DEVINL static float widen(frag8 f, int e) { return (float)__builtin_bit_cast(v8, f)[e]; }
+};
+struct F16 {
+    typedef __attribute__((ext_vector_type(8))) _Float16 v8;
+    typedef __attribute__((ext_vector_type(2))) _Float16 v2;
+    static constexpr float kRowSumLimit = 32768.0f;  // 2^15 < 65504, the largest fp16
+    DEVINL static f32x16 mfma(frag8 a, frag8 b, f32x16 c)
+    {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8, a), __builtin_bit_cast(v8, b), c, 0, 0, 0);
+    }
+    DEVINL static unsigned pack(float a, float b)
+    {
+        v2 p;
+        p[0] = (_Float16)a;
+        p[1] = (_Float16)b;
+        return __builtin_bit_cast(unsigned, p);
+    }
+    DEVINL static float add_pair(unsigned pair, float acc)
+    {
+        const v2 ones = {(_Float16)1.0f, (_Float16)1.0f};
+        return __builtin_amdgcn_fdot2(__builtin_bit_cast(v2, pair), ones, acc, false);
+    }
+    DEVINL static float widen(frag8 f, int e) { return (float)__builtin_bit_cast(v8, f)[e]; }
+};
 
 // Max of three.  Deliberately plain fmaxf, not inline assembly: the compiler inserts the wait states
 // that a vector instruction needs before it may read an MFMA result (or feed a lane permute) only
@@ -111,38 +159,26 @@ DEVINL float max16(const f32x16& s)
     return max3(m, s[15], s[15]);
 }
 
-// two fp32 -> packed bf16 pair (round to nearest even), low half = a
-DEVINL unsigned pack_bf16(float a, float b)
-{
-    bf16x2 p;
-    p[0] = (bf16)a;
-    p[1] = (bf16)b;
-    return __builtin_bit_cast(unsigned, p);
-}
-
-// accumulator registers 8*half .. 8*half+7 -> bf16 B-operand fragment of one 16-deep step
-DEVINL bf16x8 acc_to_frag(const f32x16& s, int half)
+// accumulator registers 8*half .. 8*half+7 -> B-operand fragment of one 16-deep step
+template <typename E>
+DEVINL frag8 acc_to_frag(const f32x16& s, int half)
 {
     u32x4 r;
     const int b = 8 * half;
-    r[0] = pack_bf16(s[b + 0], s[b + 1]);
-    r[1] = pack_bf16(s[b + 2], s[b + 3]);
-    r[2] = pack_bf16(s[b + 4], s[b + 5]);
-    r[3] = pack_bf16(s[b + 6], s[b + 7]);
-    return as_bf16x8(r);
+    r[0] = E::pack(s[b + 0], s[b + 1]);
+    r[1] = E::pack(s[b + 2], s[b + 3]);
+    r[2] = E::pack(s[b + 4], s[b + 5]);
+    r[3] = E::pack(s[b + 6], s[b + 7]);
+    return as_frag8(r);
 }
 
-// acc + sum of the 8 bf16 values of a fragment (fp32 accumulation, v_dot2 with a vector of ones)
-DEVINL float frag_sum(bf16x8 f, float acc)
+// acc + sum of the 8 values of a fragment (fp32 accumulation)
+template <typename E>
+DEVINL float frag_sum(frag8 f, float acc)
 {
-    const bf16x2 ones = {(bf16)1.0f, (bf16)1.0f};
+    const u32x4 w = __builtin_bit_cast(u32x4, f);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        bf16x2 pr;
-        pr[0] = f[2 * i];
-        pr[1] = f[2 * i + 1];
-        acc = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, acc, false);
-    }
+    for (int i = 0; i < 4; ++i) acc = E::add_pair(w[i], acc);
     return acc;
 }
 
@@ -156,10 +192,10 @@ struct SliceView {
     __amdgpu_buffer_rsrc_t rsrc;
     unsigned row_bytes;  // rs * 2
     unsigned bytes;      // extent of the slice
-    DEVINL SliceView(const bf16* base, long rs, int N, int D)
+    DEVINL SliceView(const raw16* base, long rs, int N, int D)
     {
         bytes = slice_bytes(rs, N, D);
-        rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16*>(base), 0, (int)bytes, 0x00020000);
+        rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<raw16*>(base), 0, (int)bytes, 0x00020000);
         row_bytes = (unsigned)(rs * 2);
     }
     DEVINL u32x4 load16(unsigned byte_off) const { return __builtin_amdgcn_raw_buffer_load_b128(rsrc, byte_off, 0, 0); }
@@ -230,9 +266,9 @@ DEVINL unsigned padded_block_voff(int blk, int lane, unsigned row_bytes)
 }
 
 // natural fragment: row `row`, 16-deep channel step `step`, lane group g
-DEVINL bf16x8 nat_frag(const char* tile, int stride, int row, int step, int g)
+DEVINL frag8 nat_frag(const char* tile, int stride, int row, int step, int g)
 {
-    return *reinterpret_cast<const bf16x8*>(tile + row * stride + step * 32 + g * 16);
+    return *reinterpret_cast<const frag8*>(tile + row * stride + step * 32 + g * 16);
 }
 
 // per-lane byte offset for transposed fragment reads (see the layout notes at the top)
@@ -242,14 +278,14 @@ DEVINL int tr_lane_offset(int lane, int stride)
     return (4 * (G >> 1) + (j >> 2)) * stride + (16 * (G & 1) + 4 * (j & 3)) * 2;
 }
 // transposed fragment: channel tile ct (32 channels), 16-token step `step`
-DEVINL bf16x8 tr_frag(const char* tile, int stride, int lane_off, int ct, int step)
+DEVINL frag8 tr_frag(const char* tile, int stride, int lane_off, int ct, int step)
 {
     const lds_char* p = (const lds_char*)tile + lane_off + step * 16 * stride + ct * 64;
     const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)p);
     const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 8 * stride));
     const u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
     const u32x4 r = {l2[0], l2[1], h2[0], h2[1]};
-    return as_bf16x8(r);
+    return as_frag8(r);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -341,7 +377,7 @@ struct TileRing {
     u32x4 desc[NPW];      // descriptor of the array the block comes from
 
     // a, b: first rows of the two [N, D] slices, whose rows are rs_a and rs_b elements apart
-    DEVINL TileRing(const bf16* a, long rs_a, const bf16* b, long rs_b, int N, const float* scalars, int npad,
+    DEVINL TileRing(const raw16* a, long rs_a, const raw16* b, long rs_b, int N, const float* scalars, int npad,
                     int ntiles_, char* smem_, int wave_, int lane)
         : smem(smem_), smem_addr(lds_address(smem_)), ntiles(ntiles_), wave(wave_)
     {
@@ -406,14 +442,14 @@ DEVINL int xcd_local_id(int block, int nblocks)
 // per-wavefront LDS region and read back so that 8 (D=64) or 10 (D=80) consecutive lanes store one
 // full row with 16-byte pieces.  `region` must not be in use by any other wavefront; LDS
 // operations of one wavefront execute in order, so no barrier is needed in between.
-template <int D>
+template <int D, typename E>
 struct RowStore {
     static constexpr int CT = (D + 31) / 32;
     static constexpr int STRIDE = D * 2 + 16;
     static constexpr int BYTES = 32 * STRIDE;  // per wavefront
     static constexpr int CH = D / 8;           // 16-byte chunks per row
 
-    DEVINL static void run(char* region, const f32x16 (&acc)[CT], float mul, bf16* dst, long rs, int rows_valid, int lane)
+    DEVINL static void run(char* region, const f32x16 (&acc)[CT], float mul, raw16* dst, long rs, int rows_valid, int lane)
     {
         const int l32 = lane % 32, g = lane / 32;
 #pragma unroll
@@ -423,8 +459,8 @@ struct RowStore {
                 const int c0 = 32 * ct + 8 * a4 + 4 * g;
                 if (c0 < D) {
                     u32x2 w;
-                    w[0] = pack_bf16(acc[ct][4 * a4 + 0] * mul, acc[ct][4 * a4 + 1] * mul);
-                    w[1] = pack_bf16(acc[ct][4 * a4 + 2] * mul, acc[ct][4 * a4 + 3] * mul);
+                    w[0] = E::pack(acc[ct][4 * a4 + 0] * mul, acc[ct][4 * a4 + 1] * mul);
+                    w[1] = E::pack(acc[ct][4 * a4 + 2] * mul, acc[ct][4 * a4 + 3] * mul);
                     *reinterpret_cast<u32x2*>(region + l32 * STRIDE + c0 * 2) = w;
                 }
             }

@@ -10,8 +10,8 @@
 // filled straight from global memory by LDS-direct loads (no staging registers, no LDS writes):
 // K rows are the A operand of S^T = K Q^T, and V is read through transposing LDS loads as the A
 // operand of O^T = V^T P^T.  Computing the transposed products keeps every score of a query inside
-// one lane pair, so the accumulator of the first contraction is, after rounding to bf16, directly
-// the B operand of the second one (no LDS round trip).
+// one lane pair, so the accumulator of the first contraction is, after rounding to the element
+// format E (bf16 or fp16), directly the B operand of the second one (no LDS round trip).
 //
 // Schedule.  A wavefront issues in order, and an MFMA queued behind another one blocks what
 // follows it, so a single wavefront cannot keep the matrix cores and the vector ALUs busy at once.
@@ -22,9 +22,10 @@
 // buffer can be refilled.
 //
 // Softmax reference.  Weights are exp2(cs*s - m) with m fixed per query to the maximum over the
-// first 32 keys.  Softmax is invariant to m, fp32/bf16 keep their relative precision at any
+// first 32 keys.  Softmax is invariant to m, floating point keeps its relative precision at any
 // magnitude, and the final division by the row sum cancels m exactly; the only failure mode is
-// overflow when a later score exceeds m by ~100 binades.  That is detected from the final row sum
+// overflow when a later score exceeds m by ~100 binades (bf16; ~15 binades for fp16, whose weights
+// must stay below 65504).  That is detected from the final row sum against E::kRowSumLimit
 // (workgroup-wide), and the whole workgroup then recomputes its rows with the classic running
 // maximum (avion_fwd_safe_pass).  Random or trained activations never get there.
 #pragma once
@@ -44,14 +45,11 @@ struct FwdCfg {
     static constexpr int WAVES_PER_SIMD = WG_PER_CU * NW / 4 > 4 ? 4 : WG_PER_CU * NW / 4;
 };
 
-// row sums above this (or not finite) send the workgroup to the safe pass
-constexpr float kRowSumLimit = 7.9e28f;  // 2^96
-
 // Classic online softmax with a running maximum, one 64-key tile at a time, staged through
 // registers into the ring's two buffers.  Used only as the fallback described above; same register
 // layouts as the main loop.
-template <int D, int NW>
-DEVINL void avion_fwd_safe_pass(char* smem, const SliceView& kh, const SliceView& vh, const bf16x8 (&qf)[D / 16],
+template <int D, int NW, typename E>
+DEVINL void avion_fwd_safe_pass(char* smem, const SliceView& kh, const SliceView& vh, const frag8 (&qf)[D / 16],
                                 f32x16 (&oacc)[(D + 31) / 32], float& m_used, float& lsum, float& rsum, int N,
                                 float cs, bool wave_active, int tid, int l32, int g, int tr_off)
 {
@@ -92,7 +90,7 @@ DEVINL void avion_fwd_safe_pass(char* smem, const SliceView& kh, const SliceView
                 f32x16 s;
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks)
-                    s = mfma32(nat_frag(kc, STRIDE, 32 * kt + l32, ks, g), qf[ks], ks == 0 ? f32x16_zero() : s);
+                    s = E::mfma(nat_frag(kc, STRIDE, 32 * kt + l32, ks, g), qf[ks], ks == 0 ? f32x16_zero() : s);
                 const int key0 = t * BN + 32 * kt + 4 * g;
                 if (key0 + 28 >= N) {
 #pragma unroll
@@ -117,13 +115,13 @@ DEVINL void avion_fwd_safe_pass(char* smem, const SliceView& kh, const SliceView
                     rowsum += p;
                 }
                 lsum += rowsum;
-                const bf16x8 pf0 = acc_to_frag(s, 0), pf1 = acc_to_frag(s, 1);
-                rsum = frag_sum(pf1, frag_sum(pf0, rsum));
+                const frag8 pf0 = acc_to_frag<E>(s, 0), pf1 = acc_to_frag<E>(s, 1);
+                rsum = frag_sum<E>(pf1, frag_sum<E>(pf0, rsum));
 #pragma unroll
                 for (int half = 0; half < 2; ++half)
 #pragma unroll
                     for (int ct = 0; ct < CT; ++ct)
-                        oacc[ct] = mfma32(tr_frag(vc, STRIDE, tr_off, ct, 2 * kt + half), half == 0 ? pf0 : pf1, oacc[ct]);
+                        oacc[ct] = E::mfma(tr_frag(vc, STRIDE, tr_off, ct, 2 * kt + half), half == 0 ? pf0 : pf1, oacc[ct]);
             }
         }
         if (more) {
@@ -134,10 +132,10 @@ DEVINL void avion_fwd_safe_pass(char* smem, const SliceView& kh, const SliceView
     }
 }
 
-template <int D, int NW>
+template <int D, int NW, typename E>
 __global__ void __launch_bounds__(NW * 64, (FwdCfg<D, NW>::WAVES_PER_SIMD))
-avion_fwd_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const bf16* __restrict__ v,
-                 bf16* __restrict__ o, float* __restrict__ lse, int H, int N, int rs_qkv, int rs_o, int nqb, int nblocks,
+avion_fwd_kernel(const raw16* __restrict__ q, const raw16* __restrict__ k, const raw16* __restrict__ v,
+                 raw16* __restrict__ o, float* __restrict__ lse, int H, int N, int rs_qkv, int rs_o, int nqb, int nblocks,
                  float cs)
 {
     using Cfg = FwdCfg<D, NW>;
@@ -168,12 +166,12 @@ avion_fwd_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const b
     ring.fetch(0);
 
     // Q fragments stay in registers for the whole kernel
-    bf16x8 qf[KS];
+    frag8 qf[KS];
     {
         const int row = min(q0 + l32, N - 1);
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
-            qf[ks] = *reinterpret_cast<const bf16x8*>(q + head_off + (long)row * rs + ks * 16 + g * 8);
+            qf[ks] = *reinterpret_cast<const frag8*>(q + head_off + (long)row * rs + ks * 16 + g * 8);
     }
     f32x16 oacc[CT];
 #pragma unroll
@@ -190,13 +188,12 @@ avion_fwd_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const b
         if constexpr (RAGGED) s = key_mask_block(key_base, g, N);
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
-            s = mfma32(nat_frag(kt, STRIDE, 32 * hk + l32, ks, g), qf[ks], ks == 0 && !RAGGED ? f32x16_zero() : s);
+            s = E::mfma(nat_frag(kt, STRIDE, 32 * hk + l32, ks, g), qf[ks], ks == 0 && !RAGGED ? f32x16_zero() : s);
         return s;
     };
     // reference maximum: over the first 32 keys
     if (wave_active) m_used = both_halves_max(max16(scores(std::true_type{}, ring.buf(0), 0, 0))) * cs;
 
-    const bf16x2 ones = {(bf16)1.0f, (bf16)1.0f};
     for (int t = 0; t < ntiles; ++t) {
         ring.fetch(t + 1);  // into the buffer of tile t-1, which nobody reads any more
         if (wave_active) {
@@ -209,7 +206,7 @@ avion_fwd_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const b
                 if (key_base + 32 > N) s = scores(std::true_type{}, kt, hk, key_base);
                 else s = scores(std::false_type{}, kt, hk, key_base);
                 // the V^T operands are requested before the vector work so that they are there after it
-                bf16x8 vf[2][CT];
+                frag8 vf[2][CT];
 #pragma unroll
                 for (int half = 0; half < 2; ++half)
 #pragma unroll
@@ -221,17 +218,17 @@ avion_fwd_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const b
                     s[i] = p;
                     lsum += p;
                     if (i % 2 == 1) {
-                        // the second row sum runs over the weights as rounded to bf16, i.e. the
+                        // the second row sum runs over the weights as rounded to the element format, i.e. the
                         // numbers the second contraction multiplies V with; O is divided by it
-                        const unsigned wgt = pack_bf16(s[i - 1], p);
+                        const unsigned wgt = E::pack(s[i - 1], p);
                         pf[i / 8][(i / 2) % 4] = wgt;
-                        rsum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, wgt), ones, rsum, false);
+                        rsum = E::add_pair(wgt, rsum);
                     }
                 }
 #pragma unroll
                 for (int half = 0; half < 2; ++half)
 #pragma unroll
-                    for (int ct = 0; ct < CT; ++ct) oacc[ct] = mfma32(vf[half][ct], as_bf16x8(pf[half]), oacc[ct]);
+                    for (int ct = 0; ct < CT; ++ct) oacc[ct] = E::mfma(vf[half][ct], as_frag8(pf[half]), oacc[ct]);
             }
         }
         Ring::landed_barrier();  // tile t+1 has landed; tile t is no longer read
@@ -239,9 +236,9 @@ avion_fwd_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const b
 
     // overflow of the fixed reference: redo this workgroup's rows with the running maximum
     bool bad = false;
-    if (wave_active) bad = !(both_halves_sum(lsum) <= kRowSumLimit);
+    if (wave_active) bad = !(both_halves_sum(lsum) <= E::kRowSumLimit);
     if (__syncthreads_or(bad ? 1 : 0))
-        avion_fwd_safe_pass<D, NW>(smem, kh, vh, qf, oacc, m_used, lsum, rsum, N, cs, wave_active, tid, l32, g, tr_off);
+        avion_fwd_safe_pass<D, NW, E>(smem, kh, vh, qf, oacc, m_used, lsum, rsum, N, cs, wave_active, tid, l32, g, tr_off);
 
     // every wavefront is past its last tile read (barrier above): the tile buffers are free and
     // serve as the per-wavefront staging area of the output rows
@@ -253,6 +250,6 @@ avion_fwd_kernel(const bf16* __restrict__ q, const bf16* __restrict__ k, const b
     for (int ct = 0; ct < CT; ++ct)
 #pragma unroll
         for (int i = 0; i < 16; ++i) oacc[ct][i] *= inv;
-    RowStore<D>::run(smem + wave * RowStore<D>::BYTES, oacc, 1.0f, o + head_off_o + (long)q0 * rs_o, rs_o, N - q0, lane);
+    RowStore<D, E>::run(smem + wave * RowStore<D, E>::BYTES, oacc, 1.0f, o + head_off_o + (long)q0 * rs_o, rs_o, N - q0, lane);
     if (g == 0 && q0 + l32 < N) lse[(long)bh * N + q0 + l32] = (m_used + __builtin_amdgcn_logf(l)) * kLn2;
 }

@@ -51,8 +51,21 @@ def bf16_bits_to_f64(b: np.ndarray) -> np.ndarray:
     return bf16_bits_to_f32(b).astype(np.float64)
 
 
-def normal_bf16_bits(seed: int, stream: int, count: int, offset: int = 0, chunk: int = 1 << 22) -> np.ndarray:
-    """`count` iid N(0,1) draws, elements offset..offset+count-1 of (seed, stream), as bf16 bits."""
+def f32_to_f16_bits(x: np.ndarray) -> np.ndarray:
+    """fp32 -> IEEE fp16 bit patterns (uint16), round to nearest even (numpy's conversion)."""
+    return np.ascontiguousarray(x, dtype=np.float32).astype(np.float16).view(np.uint16)
+
+
+def f16_bits_to_f64(b: np.ndarray) -> np.ndarray:
+    """fp16 bit patterns (uint16) -> fp64, exact."""
+    return np.ascontiguousarray(b, dtype=np.uint16).view(np.float16).astype(np.float64)
+
+
+def normal_bf16_bits(seed: int, stream: int, count: int, offset: int = 0, chunk: int = 1 << 22,
+                     to_bits=None) -> np.ndarray:
+    """`count` iid N(0,1) draws, elements offset..offset+count-1 of (seed, stream), as bf16 bits
+    (or, with to_bits=f32_to_f16_bits, the same draws rounded to fp16)."""
+    to_bits = to_bits or f32_to_bf16_bits
     out = np.empty(count, dtype=np.uint16)
     with np.errstate(over="ignore"):
         key = _mix64(np.uint64(seed & 0xFFFFFFFFFFFFFFFF) * _GOLD + np.uint64(stream + 1) * _M2)
@@ -65,7 +78,7 @@ def normal_bf16_bits(seed: int, stream: int, count: int, offset: int = 0, chunk:
             u1 = ((a >> np.uint64(11)).astype(np.float64) + 1.0) * (1.0 / 9007199254740992.0)
             u2 = (b >> np.uint64(11)).astype(np.float64) * (1.0 / 9007199254740992.0)
             z = np.sqrt(-2.0 * np.log(u1)) * np.cos((2.0 * math.pi) * u2)
-            out[start:start + n] = f32_to_bf16_bits(z.astype(np.float32))
+            out[start:start + n] = to_bits(z.astype(np.float32))
     return out
 
 
@@ -113,15 +126,24 @@ WORKLOADS = {
 STREAMS = {"q": 0, "k": 1, "v": 2, "dO": 3}
 
 
-def make_inputs(w: Workload, names=("q", "k", "v", "dO")) -> dict:
-    """bf16 bit patterns (uint16 arrays of shape [B,N,H,d]) for the requested tensors of a workload."""
+def make_inputs(w: Workload, names=("q", "k", "v", "dO"), fmt: str = "bf16") -> dict:
+    """Bit patterns (uint16 arrays of shape [B,N,H,d]) for the requested tensors of a workload, in
+    bf16 or, with fmt="f16", the same draws rounded to fp16."""
+    if fmt not in ("bf16", "f16"):
+        raise ValueError(f"unknown element format {fmt!r}")
     count = w.B * w.N * w.H * w.d
     out = {}
     for name in names:
-        bits = normal_bf16_bits(w.seed, STREAMS[name], count)
-        if name == "k" and w.k_mul != 1.0:
-            scaled = bf16_bits_to_f32(bits) * np.float32(w.k_mul)
-            bits = f32_to_bf16_bits(scaled)   # exact: a power-of-two multiple
+        if fmt == "bf16":
+            bits = normal_bf16_bits(w.seed, STREAMS[name], count)
+            if name == "k" and w.k_mul != 1.0:
+                scaled = bf16_bits_to_f32(bits) * np.float32(w.k_mul)
+                bits = f32_to_bf16_bits(scaled)   # exact: a power-of-two multiple
+        else:
+            bits = normal_bf16_bits(w.seed, STREAMS[name], count, to_bits=f32_to_f16_bits)
+            if name == "k" and w.k_mul != 1.0:
+                scaled = bits.view(np.float16).astype(np.float32) * np.float32(w.k_mul)
+                bits = f32_to_f16_bits(scaled)    # exact for these magnitudes: a power-of-two multiple
         out[name] = bits.reshape(w.shape)
     return out
 

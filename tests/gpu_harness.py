@@ -61,6 +61,59 @@ def run_hip_packed(w, x, poison=True):
     return dict(o=o, lse=lse, dq=dqkv[:, :, 0], dk=dqkv[:, :, 1], dv=dqkv[:, :, 2])
 
 
+# fp16 variant: unit roundoff 2^-11 instead of 2^-8, so the same error sources (rounding of P, dS
+# and of the outputs) are eight times smaller, and so are the bounds.
+MAX_ABS_F16 = 2.5e-3
+REL_FRO_F16 = 6.25e-4
+
+
+def run_hip_f16(w, x16):
+    """fwd + bwd through the fp16 entry points; x16 holds fp16 bit patterns."""
+    import torch
+    import paper_2309_16669_amd as av
+
+    def up(bits):
+        return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.float16)
+    q, k, v, dO = (up(x16[n]) for n in ("q", "k", "v", "dO"))
+    o = torch.full_like(q, float("nan"))
+    lse = torch.full((w.B, w.H, w.N), float("nan"), dtype=torch.float32, device="cuda")
+    dq, dk, dv = (torch.full_like(q, float("nan")) for _ in range(3))
+    ws = torch.empty(av.attn_bwd_workspace_bytes(w.B, w.H, w.N, w.d), dtype=torch.uint8, device="cuda")
+    av.attn_fwd_f16(q, k, v, o, lse, w.scale)
+    av.attn_bwd_f16(q, k, v, o, lse, dO, dq, dk, dv, w.scale, ws)
+    torch.cuda.synchronize()
+    return dict(o=o, lse=lse, dq=dq, dk=dk, dv=dv)
+
+
+def check_f16_against_oracle(w, x16, out, slices=None):
+    """fp16 results against the fp64 oracle run on the exactly widened fp16 inputs."""
+    import oracle
+    report = {}
+    sls = [(slice(None),) * 3] if slices is None else [(slice(b, b + 1), slice(None), slice(h, h + 1)) for b, h in slices]
+    for n_sl, sl in enumerate(sls):
+        q, k, v, dO = (si.f16_bits_to_f64(x16[n][sl]) for n in ("q", "k", "v", "dO"))
+        ro, rl = oracle.fwd_f64(q, k, v, w.scale)
+        rdq, rdk, rdv = oracle.bwd_f64(q, k, v, dO, w.scale)
+        tag = "" if slices is None else f"[b={slices[n_sl][0]},h={slices[n_sl][1]}]"
+        lse_gpu = out["lse"].double().cpu().numpy()
+        if slices is not None:
+            b, h = slices[n_sl]
+            lse_gpu = lse_gpu[b:b + 1, h:h + 1]
+        lse_err = float(np.abs(lse_gpu - rl).max())
+        report["LSE" + tag] = (lse_err, 0.0)
+        assert lse_err <= LSE_ABS, f"LSE{tag}: max-abs error {lse_err:.3e} > {LSE_ABS}"
+        grad_tol = REL_FRO_F16 if w.N >= 16 else REL_FRO_TINY_N / 8
+        for name, key, ref, tol in (("O", "o", ro, REL_FRO_F16), ("dQ", "dq", rdq, grad_tol), ("dK", "dk", rdk, grad_tol),
+                                    ("dV", "dv", rdv, grad_tol)):
+            got = out[key][sl].contiguous().double().cpu().numpy()
+            assert np.all(np.isfinite(got)), f"{name}{tag}: non-finite values in the GPU result"
+            max_abs, rel = errors(got, ref)
+            report[name + tag] = (max_abs, rel)
+            assert max_abs <= MAX_ABS_F16, f"{name}{tag}: max-abs error {max_abs:.3e} > {MAX_ABS_F16}"
+            assert rel <= tol, f"{name}{tag}: relative Frobenius error {rel:.3e} > {tol}"
+    return report
+
+
 def errors(gpu_f64, ref):
     diff = gpu_f64 - ref
     max_abs = float(np.abs(diff).max()) if diff.size else 0.0

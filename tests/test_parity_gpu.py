@@ -114,6 +114,51 @@ def test_longest_cls_token_shape():
     _run(si.small_workload(1, 2, 3137, 64, seed=3137, scale=0.125))
 
 
+F16_SHAPES = [(1, 1, 1, 64), (1, 2, 33, 64), (2, 3, 197, 64), (1, 2, 300, 64), (1, 2, 785, 64), (1, 1, 1569, 64),
+              (1, 1, 1, 80), (2, 2, 300, 80), (1, 1, 785, 80)]
+
+
+@pytest.mark.parametrize("B,H,N,d", F16_SHAPES)
+def test_f16_small_shapes_match_oracle(B, H, N, d):
+    w = si.small_workload(B, H, N, d, seed=1600 + 3 * N + d)
+    x = si.make_inputs(w, fmt="f16")
+    out = gh.run_hip_f16(w, x)
+    rep = gh.check_f16_against_oracle(w, x, out)
+    print(f"\nf16 {w.shape}: errors(max-abs/rel-fro)=" + str({k: f"{v[0]:.2e}/{v[1]:.2e}" for k, v in rep.items()}), flush=True)
+
+
+@pytest.mark.parametrize("name", ["vitb_batch", "vith_d80"])
+def test_f16_full_size_configs_on_sampled_heads(name):
+    import torch
+    w = si.WORKLOADS[name]
+    x = si.make_inputs(w, fmt="f16")
+    out = gh.run_hip_f16(w, x)
+    rep = gh.check_f16_against_oracle(w, x, out, [(0, 0), (w.B - 1, w.H - 1), (w.B // 2, 3)])
+    print(f"\nf16 {name}: " + str({k: f"{v[0]:.2e}/{v[1]:.2e}" for k, v in rep.items()}), flush=True)
+    for n in ("o", "dq", "dk", "dv", "lse"):
+        assert bool(torch.isfinite(out[n].float()).all()), n
+
+
+def test_f16_weights_beyond_the_half_precision_range_take_the_running_max_path():
+    # keys from 64 on are 4 times larger and scale = 1: later scores exceed the maximum over the first
+    # 32 keys by far more than 15 binades, so weights taken against that fixed reference would not
+    # fit fp16; the kernel must notice and redo the rows with a running maximum
+    import oracle
+    for d in (64, 80):
+        w = si.small_workload(1, 2, 200, d, seed=1900 + d, scale=1.0)
+        x = si.make_inputs(w, fmt="f16")
+        big = x["k"][:, 64:].view(np.float16).astype(np.float32) * np.float32(4.0)
+        x["k"][:, 64:] = si.f32_to_f16_bits(big)          # exact: power of two, far from overflow
+        out = gh.run_hip_f16(w, x)
+        q, k, v = (si.f16_bits_to_f64(x[n]) for n in ("q", "k", "v"))
+        ro, rl = oracle.fwd_f64(q, k, v, w.scale)
+        o = out["o"].double().cpu().numpy()
+        lse = out["lse"].double().cpu().numpy()
+        assert np.all(np.isfinite(o)) and np.all(np.isfinite(lse))
+        assert np.abs(o - ro).max() <= 2.0 ** -10 * np.abs(ro).max()
+        assert np.abs(lse - rl).max() <= 2e-6 * np.abs(rl).max() + 1e-3
+
+
 def test_identical_keys_and_single_token_closed_forms_on_gpu():
     # closed forms again, this time on the HIP path: identical keys -> O = mean of V
     import torch

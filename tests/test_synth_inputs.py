@@ -40,3 +40,25 @@ def test_workload_table_matches_the_token_counts():
     y = si.make_inputs(si.small_workload(1, 2, 9, 8, seed=5))
     np.testing.assert_array_equal(si.bf16_bits_to_f32(x["k"]), 2 * si.bf16_bits_to_f32(y["k"]))
     np.testing.assert_array_equal(x["q"], y["q"])
+
+
+def test_f16_inputs_are_the_same_draws_rounded_to_half_precision():
+    w = si.small_workload(2, 3, 50, 64, seed=77)
+    a = si.make_inputs(w)
+    b = si.make_inputs(w, fmt="f16")
+    for n in ("q", "k", "v", "dO"):
+        fa, fb = si.bf16_bits_to_f64(a[n]), si.f16_bits_to_f64(b[n])
+        # both are roundings of the same fp32 draw: bf16 is off by at most 2^-8 relative, fp16 by 2^-11
+        assert np.all(np.abs(fa - fb) <= (2.0 ** -8 + 2.0 ** -11) * np.abs(fb) + 1e-7)
+        assert abs(fb.std() - 1.0) < 0.05
+    assert np.array_equal(si.make_inputs(w, fmt="f16")["q"], b["q"])
+
+
+def test_f16_bit_conversions_on_known_patterns():
+    # 1.0 = 0x3C00, -2.0 = 0xC000, 65504 = 0x7BFF (largest), 2^-24 = 0x0001 (smallest subnormal);
+    # ties go to even: 1 + 2^-11 is half way between 1 and 1 + 2^-10 and rounds down to 1
+    vals = np.array([1.0, -2.0, 65504.0, 2.0 ** -24, 1.0 + 2.0 ** -11, 1.0 + 3 * 2.0 ** -11], dtype=np.float32)
+    bits = si.f32_to_f16_bits(vals)
+    assert bits.tolist() == [0x3C00, 0xC000, 0x7BFF, 0x0001, 0x3C00, 0x3C02]
+    assert si.f16_bits_to_f64(np.array([0x3C00, 0xC000, 0x7BFF, 0x0001], dtype=np.uint16)).tolist() == \
+        [1.0, -2.0, 65504.0, 2.0 ** -24]
