@@ -40,8 +40,13 @@ def _load():
         lib.avion_oracle_bwd_f64.argtypes = [p, p, p, p, p, p, p, i, i, i, i, f, i]
         lib.avion_oracle_fwd.argtypes = [p, p, p, p, p, i, i, i, i, f, i]
         lib.avion_oracle_bwd.argtypes = [p, p, p, p, p, p, p, i, i, i, i, f, i]
+        lib.avion_oracle_fwd_causal_f64.argtypes = lib.avion_oracle_fwd_f64.argtypes
+        lib.avion_oracle_bwd_causal_f64.argtypes = lib.avion_oracle_bwd_f64.argtypes
+        lib.avion_oracle_fwd_causal.argtypes = lib.avion_oracle_fwd.argtypes
+        lib.avion_oracle_bwd_causal.argtypes = lib.avion_oracle_bwd.argtypes
         for fn in (lib.avion_oracle_fwd_f64, lib.avion_oracle_bwd_f64, lib.avion_oracle_fwd,
-                   lib.avion_oracle_bwd):
+                   lib.avion_oracle_bwd, lib.avion_oracle_fwd_causal_f64, lib.avion_oracle_bwd_causal_f64,
+                   lib.avion_oracle_fwd_causal, lib.avion_oracle_bwd_causal):
             fn.restype = i
         _lib = lib
     return _lib
@@ -67,52 +72,54 @@ def _c(x, dtype):
     return np.ascontiguousarray(x, dtype=dtype)
 
 
-def fwd_f64(q, k, v, scale, want_weights=False, nthreads=0):
-    """Forward on float64 inputs. Returns (O [B,N,H,d], LSE [B,H,N]) and, if asked, P [B,H,N,N]."""
+def fwd_f64(q, k, v, scale, want_weights=False, nthreads=0, causal=False):
+    """Forward on float64 inputs. Returns (O [B,N,H,d], LSE [B,H,N]) and, if asked, P [B,H,N,N].
+    causal=True: query i attends to keys 0..i only."""
     q, k, v = _c(q, np.float64), _c(k, np.float64), _c(v, np.float64)
     B, N, H, d = _shape(q)
     assert k.shape == q.shape and v.shape == q.shape
     o = np.empty((B, N, H, d), np.float64)
     lse = np.empty((B, H, N), np.float64)
     w = np.empty((B, H, N, N), np.float64) if want_weights else None
-    _chk(_load().avion_oracle_fwd_f64(q.ctypes.data, k.ctypes.data, v.ctypes.data, o.ctypes.data,
-                                      lse.ctypes.data, w.ctypes.data if want_weights else None,
-                                      B, H, N, d, float(scale), int(nthreads)), "oracle fwd")
+    fn = _load().avion_oracle_fwd_causal_f64 if causal else _load().avion_oracle_fwd_f64
+    _chk(fn(q.ctypes.data, k.ctypes.data, v.ctypes.data, o.ctypes.data,
+            lse.ctypes.data, w.ctypes.data if want_weights else None,
+            B, H, N, d, float(scale), int(nthreads)), "oracle fwd")
     return (o, lse, w) if want_weights else (o, lse)
 
 
-def bwd_f64(q, k, v, dO, scale, nthreads=0):
+def bwd_f64(q, k, v, dO, scale, nthreads=0, causal=False):
     """Backward on float64 inputs. Returns (dQ, dK, dV), each [B,N,H,d] float64."""
     q, k, v, dO = (_c(x, np.float64) for x in (q, k, v, dO))
     B, N, H, d = _shape(q)
     assert k.shape == q.shape and v.shape == q.shape and dO.shape == q.shape
     dq, dk, dv = (np.empty((B, N, H, d), np.float64) for _ in range(3))
-    _chk(_load().avion_oracle_bwd_f64(q.ctypes.data, k.ctypes.data, v.ctypes.data, dO.ctypes.data,
-                                      dq.ctypes.data, dk.ctypes.data, dv.ctypes.data,
-                                      B, H, N, d, float(scale), int(nthreads)), "oracle bwd")
+    fn = _load().avion_oracle_bwd_causal_f64 if causal else _load().avion_oracle_bwd_f64
+    _chk(fn(q.ctypes.data, k.ctypes.data, v.ctypes.data, dO.ctypes.data, dq.ctypes.data, dk.ctypes.data, dv.ctypes.data,
+            B, H, N, d, float(scale), int(nthreads)), "oracle bwd")
     return dq, dk, dv
 
 
-def fwd(q_bits, k_bits, v_bits, scale, nthreads=0):
+def fwd(q_bits, k_bits, v_bits, scale, nthreads=0, causal=False):
     """Forward on bf16 bit patterns (uint16). Returns (O, LSE) in float64."""
     q, k, v = (_c(x, np.uint16) for x in (q_bits, k_bits, v_bits))
     B, N, H, d = _shape(q)
     assert k.shape == q.shape and v.shape == q.shape
     o = np.empty((B, N, H, d), np.float64)
     lse = np.empty((B, H, N), np.float64)
-    _chk(_load().avion_oracle_fwd(q.ctypes.data, k.ctypes.data, v.ctypes.data, o.ctypes.data,
-                                  lse.ctypes.data, B, H, N, d, float(scale), int(nthreads)),
-         "oracle fwd")
+    fn = _load().avion_oracle_fwd_causal if causal else _load().avion_oracle_fwd
+    _chk(fn(q.ctypes.data, k.ctypes.data, v.ctypes.data, o.ctypes.data, lse.ctypes.data, B, H, N, d, float(scale),
+            int(nthreads)), "oracle fwd")
     return o, lse
 
 
-def bwd(q_bits, k_bits, v_bits, dO_bits, scale, nthreads=0):
+def bwd(q_bits, k_bits, v_bits, dO_bits, scale, nthreads=0, causal=False):
     """Backward on bf16 bit patterns (uint16). Returns (dQ, dK, dV) in float64."""
     q, k, v, dO = (_c(x, np.uint16) for x in (q_bits, k_bits, v_bits, dO_bits))
     B, N, H, d = _shape(q)
     assert k.shape == q.shape and v.shape == q.shape and dO.shape == q.shape
     dq, dk, dv = (np.empty((B, N, H, d), np.float64) for _ in range(3))
-    _chk(_load().avion_oracle_bwd(q.ctypes.data, k.ctypes.data, v.ctypes.data, dO.ctypes.data,
-                                  dq.ctypes.data, dk.ctypes.data, dv.ctypes.data,
-                                  B, H, N, d, float(scale), int(nthreads)), "oracle bwd")
+    fn = _load().avion_oracle_bwd_causal if causal else _load().avion_oracle_bwd
+    _chk(fn(q.ctypes.data, k.ctypes.data, v.ctypes.data, dO.ctypes.data, dq.ctypes.data, dk.ctypes.data, dv.ctypes.data,
+            B, H, N, d, float(scale), int(nthreads)), "oracle bwd")
     return dq, dk, dv

@@ -23,6 +23,11 @@
  *              dQ_ic = scale * sum_j dS_ij k_jc
  *              dK_jc = scale * sum_i dS_ij q_ic
  *
+ * Causal variant (the *_causal entry points): the paper's text encoder is "GPT-like" (implementation
+ * details of the video-language model), i.e. token i attends to tokens 0..i only.  The definition is
+ * the same with every sum over keys j restricted to j <= i (weights of later keys are exactly 0),
+ * and the dK, dV sums over queries accordingly receive nothing from queries i < j.
+ *
  * The paper never writes these formulas; they are the textbook definition of scaled dot-product
  * attention and its analytic gradient.  The inner sum of dS is evaluated as written (not through
  * the rowsum(dO*O) shortcut a fused kernel uses), so that shortcut is itself under test.
@@ -37,6 +42,8 @@
  * N = 1; Q = 0; N = 2, d = 1 sigmoid case with hand-derived numbers; central finite differences
  * of sum(O*dO) in every coordinate of Q, K, V; gradient invariants; the block-merge identity;
  * shift and permutation invariance; agreement with a dense fp64 softmax(QK^T)V + autograd.
+ * Causal: first row returns v_0; last row equals the unmasked result; prefix property; dense masked
+ * softmax in numpy; finite differences; last key's gradients come from the last query alone.
  */
 #include <math.h>
 #include <stdint.h>
@@ -72,9 +79,10 @@ int avion_oracle_max_threads(void)
 #endif
 }
 
-/* Forward on fp64 inputs.  o: [B,N,H,d]; lse: [B,H,N]; weights: NULL or [B,H,N,N]. */
-int avion_oracle_fwd_f64(const double *q, const double *k, const double *v, double *o, double *lse,
-                         double *weights, int B, int H, int N, int d, double scale, int nthreads)
+/* Forward on fp64 inputs.  o: [B,N,H,d]; lse: [B,H,N]; weights: NULL or [B,H,N,N].
+   causal != 0: query i sees keys 0..i only. */
+static int fwd_core(const double *q, const double *k, const double *v, double *o, double *lse,
+                    double *weights, int B, int H, int N, int d, double scale, int nthreads, int causal)
 {
     if (!q || !k || !v || !o || !lse || B <= 0 || H <= 0 || N <= 0 || d <= 0) return ORACLE_EINVAL;
     if (nthreads <= 0) nthreads = avion_oracle_max_threads();
@@ -95,8 +103,9 @@ int avion_oracle_fwd_f64(const double *q, const double *k, const double *v, doub
                 int h = (int)((r / N) % H);
                 int b = (int)(r / ((long long)N * H));
                 const double *qi = q + idx4(b, i, h, N, H, d);
+                const int nk = causal ? i + 1 : N; /* keys this query sees */
                 double m = -INFINITY;
-                for (int j = 0; j < N; ++j) {
+                for (int j = 0; j < nk; ++j) {
                     const double *kj = k + idx4(b, j, h, N, H, d);
                     double acc = 0.0;
                     for (int c = 0; c < d; ++c) acc += qi[c] * kj[c];
@@ -104,18 +113,20 @@ int avion_oracle_fwd_f64(const double *q, const double *k, const double *v, doub
                     if (s[j] > m) m = s[j];
                 }
                 double l = 0.0;
-                for (int j = 0; j < N; ++j) {
+                for (int j = 0; j < nk; ++j) {
                     s[j] = exp(s[j] - m);
                     l += s[j];
                 }
                 double *oi = o + idx4(b, i, h, N, H, d);
                 for (int c = 0; c < d; ++c) oi[c] = 0.0;
-                for (int j = 0; j < N; ++j) {
+                for (int j = 0; j < nk; ++j) {
                     double p = s[j] / l;
                     const double *vj = v + idx4(b, j, h, N, H, d);
                     for (int c = 0; c < d; ++c) oi[c] += p * vj[c];
                     if (weights) weights[(((size_t)b * H + h) * N + i) * (size_t)N + j] = p;
                 }
+                if (weights)
+                    for (int j = nk; j < N; ++j) weights[(((size_t)b * H + h) * N + i) * (size_t)N + j] = 0.0;
                 lse[((size_t)b * H + h) * N + i] = m + log(l);
             }
         }
@@ -124,11 +135,23 @@ int avion_oracle_fwd_f64(const double *q, const double *k, const double *v, doub
     return failed ? ORACLE_ENOMEM : ORACLE_OK;
 }
 
+int avion_oracle_fwd_f64(const double *q, const double *k, const double *v, double *o, double *lse,
+                         double *weights, int B, int H, int N, int d, double scale, int nthreads)
+{
+    return fwd_core(q, k, v, o, lse, weights, B, H, N, d, scale, nthreads, 0);
+}
+
+int avion_oracle_fwd_causal_f64(const double *q, const double *k, const double *v, double *o, double *lse,
+                                double *weights, int B, int H, int N, int d, double scale, int nthreads)
+{
+    return fwd_core(q, k, v, o, lse, weights, B, H, N, d, scale, nthreads, 1);
+}
+
 /* Backward on fp64 inputs, from the definition (P is rebuilt from q, k; o and lse are not inputs).
-   dq, dk, dv: [B,N,H,d], fully overwritten. */
-int avion_oracle_bwd_f64(const double *q, const double *k, const double *v, const double *dO,
-                         double *dq, double *dk, double *dv, int B, int H, int N, int d,
-                         double scale, int nthreads)
+   dq, dk, dv: [B,N,H,d], fully overwritten.  causal != 0: query i sees keys 0..i only. */
+static int bwd_core(const double *q, const double *k, const double *v, const double *dO,
+                    double *dq, double *dk, double *dv, int B, int H, int N, int d,
+                    double scale, int nthreads, int causal)
 {
     if (!q || !k || !v || !dO || !dq || !dk || !dv || B <= 0 || H <= 0 || N <= 0 || d <= 0)
         return ORACLE_EINVAL;
@@ -163,8 +186,9 @@ int avion_oracle_bwd_f64(const double *q, const double *k, const double *v, cons
                 for (int i = 0; i < N; ++i) {
                     const double *qi = q + idx4(b, i, h, N, H, d);
                     const double *doi = dO + idx4(b, i, h, N, H, d);
+                    const int nk = causal ? i + 1 : N; /* keys this query sees */
                     double m = -INFINITY;
-                    for (int j = 0; j < N; ++j) {
+                    for (int j = 0; j < nk; ++j) {
                         const double *kj = k + idx4(b, j, h, N, H, d);
                         double acc = 0.0;
                         for (int c = 0; c < d; ++c) acc += qi[c] * kj[c];
@@ -172,12 +196,12 @@ int avion_oracle_bwd_f64(const double *q, const double *k, const double *v, cons
                         if (p[j] > m) m = p[j];
                     }
                     double l = 0.0;
-                    for (int j = 0; j < N; ++j) {
+                    for (int j = 0; j < nk; ++j) {
                         p[j] = exp(p[j] - m);
                         l += p[j];
                     }
                     double inner = 0.0; /* sum_k P_ik dP_ik */
-                    for (int j = 0; j < N; ++j) {
+                    for (int j = 0; j < nk; ++j) {
                         p[j] /= l;
                         const double *vj = v + idx4(b, j, h, N, H, d);
                         double acc = 0.0;
@@ -187,7 +211,7 @@ int avion_oracle_bwd_f64(const double *q, const double *k, const double *v, cons
                     }
                     double *dqi = dq + idx4(b, i, h, N, H, d);
                     for (int c = 0; c < d; ++c) dqi[c] = 0.0;
-                    for (int j = 0; j < N; ++j) {
+                    for (int j = 0; j < nk; ++j) {
                         double ds = p[j] * (g[j] - inner);
                         const double *kj = k + idx4(b, j, h, N, H, d);
                         double *dkj = pdk + (size_t)j * d;
@@ -224,6 +248,20 @@ int avion_oracle_bwd_f64(const double *q, const double *k, const double *v, cons
     return ORACLE_OK;
 }
 
+int avion_oracle_bwd_f64(const double *q, const double *k, const double *v, const double *dO,
+                         double *dq, double *dk, double *dv, int B, int H, int N, int d,
+                         double scale, int nthreads)
+{
+    return bwd_core(q, k, v, dO, dq, dk, dv, B, H, N, d, scale, nthreads, 0);
+}
+
+int avion_oracle_bwd_causal_f64(const double *q, const double *k, const double *v, const double *dO,
+                                double *dq, double *dk, double *dv, int B, int H, int N, int d,
+                                double scale, int nthreads)
+{
+    return bwd_core(q, k, v, dO, dq, dk, dv, B, H, N, d, scale, nthreads, 1);
+}
+
 static double *widen(const uint16_t *x, size_t n)
 {
     double *y = (double *)malloc(sizeof(double) * n);
@@ -233,17 +271,46 @@ static double *widen(const uint16_t *x, size_t n)
 }
 
 /* Same as the fp64 entry points, on bf16 bit patterns (widened exactly). Outputs stay fp64. */
-int avion_oracle_fwd(const uint16_t *q, const uint16_t *k, const uint16_t *v, double *o, double *lse,
-                     int B, int H, int N, int d, double scale, int nthreads)
+static int fwd_bits(const uint16_t *q, const uint16_t *k, const uint16_t *v, double *o, double *lse,
+                    int B, int H, int N, int d, double scale, int nthreads, int causal)
 {
     if (!q || !k || !v || B <= 0 || H <= 0 || N <= 0 || d <= 0) return ORACLE_EINVAL;
     size_t n = (size_t)B * N * H * d;
     double *qd = widen(q, n), *kd = widen(k, n), *vd = widen(v, n);
     int rc = ORACLE_ENOMEM;
-    if (qd && kd && vd) rc = avion_oracle_fwd_f64(qd, kd, vd, o, lse, NULL, B, H, N, d, scale, nthreads);
+    if (qd && kd && vd) rc = fwd_core(qd, kd, vd, o, lse, NULL, B, H, N, d, scale, nthreads, causal);
     free(qd);
     free(kd);
     free(vd);
+    return rc;
+}
+
+int avion_oracle_fwd(const uint16_t *q, const uint16_t *k, const uint16_t *v, double *o, double *lse,
+                     int B, int H, int N, int d, double scale, int nthreads)
+{
+    return fwd_bits(q, k, v, o, lse, B, H, N, d, scale, nthreads, 0);
+}
+
+int avion_oracle_fwd_causal(const uint16_t *q, const uint16_t *k, const uint16_t *v, double *o, double *lse,
+                            int B, int H, int N, int d, double scale, int nthreads)
+{
+    return fwd_bits(q, k, v, o, lse, B, H, N, d, scale, nthreads, 1);
+}
+
+static int bwd_bits(const uint16_t *q, const uint16_t *k, const uint16_t *v, const uint16_t *dO,
+                    double *dq, double *dk, double *dv, int B, int H, int N, int d, double scale,
+                    int nthreads, int causal)
+{
+    if (!q || !k || !v || !dO || B <= 0 || H <= 0 || N <= 0 || d <= 0) return ORACLE_EINVAL;
+    size_t n = (size_t)B * N * H * d;
+    double *qd = widen(q, n), *kd = widen(k, n), *vd = widen(v, n), *gd = widen(dO, n);
+    int rc = ORACLE_ENOMEM;
+    if (qd && kd && vd && gd)
+        rc = bwd_core(qd, kd, vd, gd, dq, dk, dv, B, H, N, d, scale, nthreads, causal);
+    free(qd);
+    free(kd);
+    free(vd);
+    free(gd);
     return rc;
 }
 
@@ -251,15 +318,12 @@ int avion_oracle_bwd(const uint16_t *q, const uint16_t *k, const uint16_t *v, co
                      double *dq, double *dk, double *dv, int B, int H, int N, int d, double scale,
                      int nthreads)
 {
-    if (!q || !k || !v || !dO || B <= 0 || H <= 0 || N <= 0 || d <= 0) return ORACLE_EINVAL;
-    size_t n = (size_t)B * N * H * d;
-    double *qd = widen(q, n), *kd = widen(k, n), *vd = widen(v, n), *gd = widen(dO, n);
-    int rc = ORACLE_ENOMEM;
-    if (qd && kd && vd && gd)
-        rc = avion_oracle_bwd_f64(qd, kd, vd, gd, dq, dk, dv, B, H, N, d, scale, nthreads);
-    free(qd);
-    free(kd);
-    free(vd);
-    free(gd);
-    return rc;
+    return bwd_bits(q, k, v, dO, dq, dk, dv, B, H, N, d, scale, nthreads, 0);
+}
+
+int avion_oracle_bwd_causal(const uint16_t *q, const uint16_t *k, const uint16_t *v, const uint16_t *dO,
+                            double *dq, double *dk, double *dv, int B, int H, int N, int d, double scale,
+                            int nthreads)
+{
+    return bwd_bits(q, k, v, dO, dq, dk, dv, B, H, N, d, scale, nthreads, 1);
 }

@@ -294,3 +294,106 @@ def test_large_scores_do_not_overflow():
     # three keys tie at s = 1800, one is at -1800 (weight exactly 0 in fp64)
     np.testing.assert_allclose(o[0, 0, 0], v[0, [0, 1, 3], 0].mean(0), atol=1e-13)
     np.testing.assert_allclose(lse, 1800.0 + math.log(3.0), atol=1e-10)
+
+
+# ================================================================ causal variant (GPT-like text encoder)
+# ---------------------------------------------------------------- C1: closed forms of the first and last rows
+def test_causal_first_row_is_v0_and_last_row_is_unmasked():
+    B, N, H, d = 2, 23, 3, 5
+    q, k, v = rand(B, N, H, d, 1.5), rand(B, N, H, d, 1.5), rand(B, N, H, d)
+    scale = 0.4
+    o, lse, p = oracle.fwd_f64(q, k, v, scale, want_weights=True, causal=True)
+    # token 0 sees only itself: O_0 = v_0 and LSE_0 = s_00
+    np.testing.assert_allclose(o[:, 0], v[:, 0], rtol=0, atol=1e-15)
+    np.testing.assert_allclose(lse[:, :, 0], scale * np.einsum("bhc,bhc->bh", q[:, 0], k[:, 0]), rtol=0, atol=1e-13)
+    # the last token sees every key: same as the unmasked operation
+    o_full, lse_full = oracle.fwd_f64(q, k, v, scale)
+    np.testing.assert_allclose(o[:, -1], o_full[:, -1], rtol=0, atol=1e-14)
+    np.testing.assert_allclose(lse[:, :, -1], lse_full[:, :, -1], rtol=0, atol=1e-13)
+    # weights: zero above the diagonal, a distribution over the visible keys
+    assert np.all(np.triu(p, 1) == 0.0)
+    np.testing.assert_allclose(p.sum(-1), 1.0, rtol=0, atol=1e-12)
+
+
+# ---------------------------------------------------------------- C2: prefix property
+@pytest.mark.parametrize("M", [1, 6, 17])
+def test_causal_prefix_does_not_depend_on_later_tokens(M):
+    B, N, H, d = 1, 30, 2, 4
+    q, k, v, dO = rand(B, N, H, d), rand(B, N, H, d), rand(B, N, H, d), rand(B, N, H, d)
+    o, lse = oracle.fwd_f64(q, k, v, 0.5, causal=True)
+    om, lsem = oracle.fwd_f64(q[:, :M], k[:, :M], v[:, :M], 0.5, causal=True)
+    np.testing.assert_allclose(o[:, :M], om, rtol=0, atol=1e-14)
+    np.testing.assert_allclose(lse[:, :, :M], lsem, rtol=0, atol=1e-13)
+    # and the gradient with respect to the first M queries, when only their outputs carry gradient
+    g = dO.copy()
+    g[:, M:] = 0.0
+    dq, dk, dv = oracle.bwd_f64(q, k, v, g, 0.5, causal=True)
+    dqm, dkm, dvm = oracle.bwd_f64(q[:, :M], k[:, :M], v[:, :M], dO[:, :M], 0.5, causal=True)
+    np.testing.assert_allclose(dq[:, :M], dqm, rtol=0, atol=1e-13)
+    np.testing.assert_allclose(dk[:, :M], dkm, rtol=0, atol=1e-13)
+    np.testing.assert_allclose(dv[:, :M], dvm, rtol=0, atol=1e-13)
+    assert np.all(dq[:, M:] == 0.0) and np.all(dk[:, M:] == 0.0) and np.all(dv[:, M:] == 0.0)
+
+
+# ---------------------------------------------------------------- C3: dense masked softmax + autograd
+@pytest.mark.parametrize("B,N,H,d", [(2, 1, 2, 8), (2, 50, 3, 16), (1, 77, 2, 64)])
+def test_causal_matches_dense_masked_softmax_and_autograd(B, N, H, d):
+    torch = pytest.importorskip("torch")
+    q, k, v, dO = rand(B, N, H, d), rand(B, N, H, d), rand(B, N, H, d), rand(B, N, H, d)
+    scale = 1.0 / math.sqrt(d)
+    tq, tk, tv = (torch.tensor(x, dtype=torch.float64, requires_grad=True) for x in (q, k, v))
+    s = torch.einsum("bnhc,bmhc->bhnm", tq, tk) * scale
+    s = s.masked_fill(torch.triu(torch.ones(N, N, dtype=torch.bool), diagonal=1), float("-inf"))
+    to = torch.einsum("bhnm,bmhc->bnhc", torch.softmax(s, dim=-1), tv)
+    to.backward(torch.tensor(dO))
+    o, lse = oracle.fwd_f64(q, k, v, scale, causal=True)
+    dq, dk, dv = oracle.bwd_f64(q, k, v, dO, scale, causal=True)
+    np.testing.assert_allclose(o, to.detach().numpy(), atol=1e-12)
+    np.testing.assert_allclose(lse, torch.logsumexp(s, dim=-1).detach().numpy(), atol=1e-12)
+    np.testing.assert_allclose(dq, tq.grad.numpy(), atol=1e-11)
+    np.testing.assert_allclose(dk, tk.grad.numpy(), atol=1e-11)
+    np.testing.assert_allclose(dv, tv.grad.numpy(), atol=1e-11)
+
+
+# ---------------------------------------------------------------- C4: finite differences, last key's closed form
+def test_causal_gradients_match_central_differences_and_last_key_closed_form():
+    B, N, H, d, scale = 1, 6, 2, 3, 0.7
+    q, k, v, dO = rand(B, N, H, d), rand(B, N, H, d), rand(B, N, H, d), rand(B, N, H, d)
+    dq, dk, dv = oracle.bwd_f64(q, k, v, dO, scale, causal=True)
+    _, _, p = oracle.fwd_f64(q, k, v, scale, want_weights=True, causal=True)
+    # only the last query sees the last key: dV_last = P_last,last * dO_last
+    np.testing.assert_allclose(dv[:, -1], p[:, :, -1, -1][..., None] * dO[:, -1], rtol=0, atol=1e-14)
+
+    def loss(q_, k_, v_):
+        o, _ = oracle.fwd_f64(q_, k_, v_, scale, nthreads=1, causal=True)
+        return float((o * dO).sum())
+
+    h = 1e-6
+    for name, x, grad in (("q", q, dq), ("k", k, dk), ("v", v, dv)):
+        num = np.zeros_like(x)
+        it = np.nditer(x, flags=["multi_index"])
+        for _ in it:
+            idx = it.multi_index
+            xp, xm = x.copy(), x.copy()
+            xp[idx] += h
+            xm[idx] -= h
+            a_p = {"q": q, "k": k, "v": v}
+            a_m = dict(a_p)
+            a_p[name], a_m[name] = xp, xm
+            num[idx] = (loss(a_p["q"], a_p["k"], a_p["v"]) - loss(a_m["q"], a_m["k"], a_m["v"])) / (2 * h)
+        denom = max(np.abs(num).max(), 1e-3)
+        assert np.abs(num - grad).max() / denom < 1e-6, name
+
+
+def test_causal_bf16_entry_points_widen_exactly():
+    import synth_inputs as si
+    w = si.small_workload(2, 2, 45, 16, seed=8)
+    x = si.make_inputs(w)
+    f = {n: si.bf16_bits_to_f64(x[n]) for n in x}
+    o1, l1 = oracle.fwd(x["q"], x["k"], x["v"], w.scale, causal=True)
+    o2, l2 = oracle.fwd_f64(f["q"], f["k"], f["v"], w.scale, causal=True)
+    assert np.array_equal(o1, o2) and np.array_equal(l1, l2)
+    g1 = oracle.bwd(x["q"], x["k"], x["v"], x["dO"], w.scale, causal=True)
+    g2 = oracle.bwd_f64(f["q"], f["k"], f["v"], f["dO"], w.scale, causal=True)
+    for a, b in zip(g1, g2):
+        assert np.array_equal(a, b)
