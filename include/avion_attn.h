@@ -153,6 +153,23 @@ int avion_attn_bwd_f16(const void *q, const void *k, const void *v, const void *
                        int B, int H, int N, int d, float scale,
                        void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * Causal variants, for the text side of the paper's video-language model: its text encoder is a
+ * GPT-like Transformer over at most 77 tokens (implementation details of the video-language model),
+ * i.e. token i attends to tokens 0..i.  Same tensors, layouts, workspace and rules as
+ * avion_attn_fwd / avion_attn_bwd (bf16); the softmax of query i runs over keys j <= i only:
+ *     P_ij = exp(s_ij - LSE_i) for j <= i, 0 otherwise;  LSE_i = ln sum_{j<=i} exp(s_ij)
+ * and every formula of the header's first comment holds with that P.  Blocks of keys that no query
+ * of a wavefront sees are skipped, blocks on the diagonal are masked; nothing N x N is stored.
+ */
+int avion_attn_fwd_causal(const void *q, const void *k, const void *v, void *o, float *lse,
+                          int B, int H, int N, int d, float scale, void *stream);
+
+int avion_attn_bwd_causal(const void *q, const void *k, const void *v, const void *o,
+                          const float *lse, const void *dO, void *dq, void *dk, void *dv,
+                          int B, int H, int N, int d, float scale,
+                          void *workspace, size_t workspace_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -59,6 +59,10 @@ def load_library() -> ctypes.CDLL:
         lib.avion_attn_fwd_f16.argtypes = lib.avion_attn_fwd.argtypes
         lib.avion_attn_bwd_f16.restype = i
         lib.avion_attn_bwd_f16.argtypes = lib.avion_attn_bwd.argtypes
+        lib.avion_attn_fwd_causal.restype = i
+        lib.avion_attn_fwd_causal.argtypes = lib.avion_attn_fwd.argtypes
+        lib.avion_attn_bwd_causal.restype = i
+        lib.avion_attn_bwd_causal.argtypes = lib.avion_attn_bwd.argtypes
         _lib = lib
     return _lib
 
@@ -148,6 +152,19 @@ def attn_bwd_f16(q, k, v, o, lse, dO, dq, dk, dv, scale: float, workspace, strea
     """avion_attn_bwd_f16: the same on fp16 tensors."""
     import torch
     _bwd(load_library().avion_attn_bwd_f16, torch.float16, q, k, v, o, lse, dO, dq, dk, dv, scale, workspace, stream)
+
+
+def attn_fwd_causal(q, k, v, o, lse, scale: float, stream=None) -> None:
+    """avion_attn_fwd_causal: bf16 tensors, query i attends to keys 0..i."""
+    import torch
+    _fwd(load_library().avion_attn_fwd_causal, torch.bfloat16, q, k, v, o, lse, scale, stream)
+
+
+def attn_bwd_causal(q, k, v, o, lse, dO, dq, dk, dv, scale: float, workspace, stream=None) -> None:
+    """avion_attn_bwd_causal: gradients of the causal forward."""
+    import torch
+    _bwd(load_library().avion_attn_bwd_causal, torch.bfloat16, q, k, v, o, lse, dO, dq, dk, dv, scale, workspace,
+         stream)
 
 
 def attn_bwd_dq(q, k, v, o, lse, dO, dq, scale: float, workspace, stream=None) -> None:

@@ -31,6 +31,12 @@ struct Strides {
     int o;    // O and dO: H*d
 };
 
+// Which kernel family an entry point runs: element format and masking.
+struct Variant {
+    bool f16;
+    bool causal;
+};
+
 int check_shape(int B, int H, int N, int d, float scale, int packed = 1)
 {
     if (B < 1 || H < 1 || N < 1) return AVION_EINVAL;
@@ -58,60 +64,81 @@ hipError_t allow_lds(K kernel, int bytes)
     return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
 }
 
-template <int D, int NW, typename E>
+template <int D, int NW, typename E, bool CAUSAL>
 int launch_fwd(const raw16* q, const raw16* k, const raw16* v, raw16* o, float* lse, int B, int H, int N, Strides rs,
                float scale, hipStream_t st)
 {
     using Cfg = FwdCfg<D, NW>;
-    static hipError_t attr = allow_lds(avion_fwd_kernel<D, NW, E>, Cfg::LDS_BYTES);
+    static hipError_t attr = allow_lds(avion_fwd_kernel<D, NW, E, CAUSAL>, Cfg::LDS_BYTES);
     if (attr != hipSuccess) return hip_fail(attr, "hipFuncSetAttribute(fwd)");
     const int nqb = (N + Cfg::BM - 1) / Cfg::BM;
     const long long nblocks = (long long)nqb * B * H;
     unsigned grid;
     if (!grid_for(nblocks, &grid)) return AVION_EUNSUPPORTED;
-    hipLaunchKernelGGL((avion_fwd_kernel<D, NW, E>), dim3(grid), dim3(Cfg::NT), Cfg::LDS_BYTES, st, q, k, v, o, lse, H, N, rs.qkv,
+    hipLaunchKernelGGL((avion_fwd_kernel<D, NW, E, CAUSAL>), dim3(grid), dim3(Cfg::NT), Cfg::LDS_BYTES, st, q, k, v, o, lse, H, N, rs.qkv,
                        rs.o, nqb, (int)nblocks, scale * kLog2e);
     const hipError_t e = hipGetLastError();
     return e == hipSuccess ? AVION_OK : hip_fail(e, "launch avion_fwd_kernel");
 }
 
-template <int D, int NW, typename E>
+template <int D, int NW, typename E, bool CAUSAL>
 int launch_dq(const raw16* q, const raw16* k, const raw16* v, const raw16* o, const raw16* dO, const float* lse, raw16* dq,
               float* rowsc, int B, int H, int N, Strides rs, float scale, hipStream_t st)
 {
     using Cfg = DqCfg<D, NW>;
-    static hipError_t attr = allow_lds(avion_dq_kernel<D, NW, E>, Cfg::LDS_BYTES);
+    static hipError_t attr = allow_lds(avion_dq_kernel<D, NW, E, CAUSAL>, Cfg::LDS_BYTES);
     if (attr != hipSuccess) return hip_fail(attr, "hipFuncSetAttribute(dq)");
     const int nqb = (N + Cfg::BM - 1) / Cfg::BM;
     const long long nblocks = (long long)nqb * B * H;
     unsigned grid;
     if (!grid_for(nblocks, &grid)) return AVION_EUNSUPPORTED;
-    hipLaunchKernelGGL((avion_dq_kernel<D, NW, E>), dim3(grid), dim3(Cfg::NT), Cfg::LDS_BYTES, st, q, k, v, o, dO, lse, dq,
+    hipLaunchKernelGGL((avion_dq_kernel<D, NW, E, CAUSAL>), dim3(grid), dim3(Cfg::NT), Cfg::LDS_BYTES, st, q, k, v, o, dO, lse, dq,
                        rowsc, H, N, rs.qkv, rs.o, nqb, (int)nblocks, scale * kLog2e, scale);
     const hipError_t e = hipGetLastError();
     return e == hipSuccess ? AVION_OK : hip_fail(e, "launch avion_dq_kernel");
 }
 
-template <int D, int NW, typename E>
+template <int D, int NW, typename E, bool CAUSAL>
 int launch_dkdv(const raw16* q, const raw16* k, const raw16* v, const raw16* dO, const float* rowsc, raw16* dk, raw16* dv,
                 int B, int H, int N, Strides rs, float scale, hipStream_t st)
 {
     using Cfg = DkvCfg<D, NW>;
-    static hipError_t attr = allow_lds(avion_dkdv_kernel<D, NW, E>, Cfg::LDS_BYTES);
+    static hipError_t attr = allow_lds(avion_dkdv_kernel<D, NW, E, CAUSAL>, Cfg::LDS_BYTES);
     if (attr != hipSuccess) return hip_fail(attr, "hipFuncSetAttribute(dkdv)");
     const int nkb = (N + Cfg::BNK - 1) / Cfg::BNK;
     const long long nblocks = (long long)nkb * B * H;
     unsigned grid;
     if (!grid_for(nblocks, &grid)) return AVION_EUNSUPPORTED;
-    hipLaunchKernelGGL((avion_dkdv_kernel<D, NW, E>), dim3(grid), dim3(Cfg::NT), Cfg::LDS_BYTES, st, q, k, v, dO, rowsc, dk,
+    hipLaunchKernelGGL((avion_dkdv_kernel<D, NW, E, CAUSAL>), dim3(grid), dim3(Cfg::NT), Cfg::LDS_BYTES, st, q, k, v, dO, rowsc, dk,
                        dv, H, N, rs.qkv, rs.o, nkb, (int)nblocks, scale * kLog2e, scale);
     const hipError_t e = hipGetLastError();
     return e == hipSuccess ? AVION_OK : hip_fail(e, "launch avion_dkdv_kernel");
 }
 
-// Kernel instances: four wavefronts per workgroup for every kernel and head size.
+// Kernel instances: four wavefronts per workgroup for every kernel, head size, format and masking.
+// Calls f(head dim, element format, causal) with the three as compile-time tags.
+template <typename T>
+struct TypeTag {
+    using type = T;
+};
+template <typename F>
+int by_variant(Variant var, int d, F f)
+{
+    auto by_dim = [&](auto fmt, auto causal) {
+        if (d == 64) return f(std::integral_constant<int, 64>{}, fmt, causal);
+        return f(std::integral_constant<int, 80>{}, fmt, causal);
+    };
+    auto by_fmt = [&](auto causal) {
+        if (var.f16) return by_dim(TypeTag<F16>{}, causal);
+        return by_dim(TypeTag<Bf16>{}, causal);
+    };
+    if (var.causal) return by_fmt(std::true_type{});
+    return by_fmt(std::false_type{});
+}
+
+
 int fwd_impl(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int N, int d, int packed,
-             bool f16, float scale, void* stream)
+             Variant var, float scale, void* stream)
 {
     if (!q || !k || !v || !o || !lse) return AVION_EINVAL;
     const int rc = check_shape(B, H, N, d, scale, packed);
@@ -121,12 +148,10 @@ int fwd_impl(const void* q, const void* k, const void* v, void* o, float* lse, i
     const Strides rs{packed * H * d, H * d};
     const raw16 *qq = static_cast<const raw16*>(q), *kk = static_cast<const raw16*>(k), *vv = static_cast<const raw16*>(v);
     raw16* oo = static_cast<raw16*>(o);
-    if (f16) {
-        if (d == 64) return launch_fwd<64, 4, F16>(qq, kk, vv, oo, lse, B, H, N, rs, scale, st);
-        return launch_fwd<80, 4, F16>(qq, kk, vv, oo, lse, B, H, N, rs, scale, st);
-    }
-    if (d == 64) return launch_fwd<64, 4, Bf16>(qq, kk, vv, oo, lse, B, H, N, rs, scale, st);
-    return launch_fwd<80, 4, Bf16>(qq, kk, vv, oo, lse, B, H, N, rs, scale, st);
+    return by_variant(var, d, [&](auto dim, auto fmt, auto causal) {
+        return launch_fwd<decltype(dim)::value, 4, typename decltype(fmt)::type, decltype(causal)::value>(
+            qq, kk, vv, oo, lse, B, H, N, rs, scale, st);
+    });
 }
 
 bool workspace_ok(const void* workspace, size_t workspace_bytes, int B, int H, int N, int d)
@@ -136,7 +161,7 @@ bool workspace_ok(const void* workspace, size_t workspace_bytes, int B, int H, i
 }
 
 int dq_impl(const void* q, const void* k, const void* v, const void* o, const float* lse, const void* dO, void* dq, int B,
-            int H, int N, int d, int packed, bool f16, float scale, void* workspace, size_t workspace_bytes, void* stream)
+            int H, int N, int d, int packed, Variant var, float scale, void* workspace, size_t workspace_bytes, void* stream)
 {
     if (!q || !k || !v || !o || !lse || !dO || !dq) return AVION_EINVAL;
     const int rc = check_shape(B, H, N, d, scale, packed);
@@ -151,16 +176,14 @@ int dq_impl(const void* q, const void* k, const void* v, const void* o, const fl
     const raw16 *qq = static_cast<const raw16*>(q), *kk = static_cast<const raw16*>(k), *vv = static_cast<const raw16*>(v),
                *oo = static_cast<const raw16*>(o), *gg = static_cast<const raw16*>(dO);
     raw16* dqq = static_cast<raw16*>(dq);
-    if (f16) {
-        if (d == 64) return launch_dq<64, 4, F16>(qq, kk, vv, oo, gg, lse, dqq, rowsc, B, H, N, rs, scale, st);
-        return launch_dq<80, 4, F16>(qq, kk, vv, oo, gg, lse, dqq, rowsc, B, H, N, rs, scale, st);
-    }
-    if (d == 64) return launch_dq<64, 4, Bf16>(qq, kk, vv, oo, gg, lse, dqq, rowsc, B, H, N, rs, scale, st);
-    return launch_dq<80, 4, Bf16>(qq, kk, vv, oo, gg, lse, dqq, rowsc, B, H, N, rs, scale, st);
+    return by_variant(var, d, [&](auto dim, auto fmt, auto causal) {
+        return launch_dq<decltype(dim)::value, 4, typename decltype(fmt)::type, decltype(causal)::value>(
+            qq, kk, vv, oo, gg, lse, dqq, rowsc, B, H, N, rs, scale, st);
+    });
 }
 
 int dkdv_impl(const void* q, const void* k, const void* v, const float* lse, const void* dO, void* dk, void* dv, int B,
-              int H, int N, int d, int packed, bool f16, float scale, const void* workspace, size_t workspace_bytes,
+              int H, int N, int d, int packed, Variant var, float scale, const void* workspace, size_t workspace_bytes,
               void* stream)
 {
     if (!q || !k || !v || !lse || !dO || !dk || !dv) return AVION_EINVAL;
@@ -176,16 +199,14 @@ int dkdv_impl(const void* q, const void* k, const void* v, const float* lse, con
     const raw16 *qq = static_cast<const raw16*>(q), *kk = static_cast<const raw16*>(k), *vv = static_cast<const raw16*>(v),
                *gg = static_cast<const raw16*>(dO);
     raw16 *dkk = static_cast<raw16*>(dk), *dvv = static_cast<raw16*>(dv);
-    if (f16) {
-        if (d == 64) return launch_dkdv<64, 4, F16>(qq, kk, vv, gg, rowsc, dkk, dvv, B, H, N, rs, scale, st);
-        return launch_dkdv<80, 4, F16>(qq, kk, vv, gg, rowsc, dkk, dvv, B, H, N, rs, scale, st);
-    }
-    if (d == 64) return launch_dkdv<64, 4, Bf16>(qq, kk, vv, gg, rowsc, dkk, dvv, B, H, N, rs, scale, st);
-    return launch_dkdv<80, 4, Bf16>(qq, kk, vv, gg, rowsc, dkk, dvv, B, H, N, rs, scale, st);
+    return by_variant(var, d, [&](auto dim, auto fmt, auto causal) {
+        return launch_dkdv<decltype(dim)::value, 4, typename decltype(fmt)::type, decltype(causal)::value>(
+            qq, kk, vv, gg, rowsc, dkk, dvv, B, H, N, rs, scale, st);
+    });
 }
 
 int bwd_impl(const void* q, const void* k, const void* v, const void* o, const float* lse, const void* dO, void* dq,
-             void* dk, void* dv, int B, int H, int N, int d, bool f16, float scale, void* workspace, size_t workspace_bytes,
+             void* dk, void* dv, int B, int H, int N, int d, Variant var, float scale, void* workspace, size_t workspace_bytes,
              void* stream)
 {
     // every argument is checked before the first launch, so an error leaves all outputs untouched
@@ -196,9 +217,9 @@ int bwd_impl(const void* q, const void* k, const void* v, const void* o, const f
     for (const void* p : ptrs)
         if (!aligned16(p)) return AVION_EUNSUPPORTED;
     if (!workspace_ok(workspace, workspace_bytes, B, H, N, d)) return AVION_EWORKSPACE;
-    const int rq = dq_impl(q, k, v, o, lse, dO, dq, B, H, N, d, 1, f16, scale, workspace, workspace_bytes, stream);
+    const int rq = dq_impl(q, k, v, o, lse, dO, dq, B, H, N, d, 1, var, scale, workspace, workspace_bytes, stream);
     if (rq != AVION_OK) return rq;
-    return dkdv_impl(q, k, v, lse, dO, dk, dv, B, H, N, d, 1, f16, scale, workspace, workspace_bytes, stream);
+    return dkdv_impl(q, k, v, lse, dO, dk, dv, B, H, N, d, 1, var, scale, workspace, workspace_bytes, stream);
 }
 
 // q, k, v planes of a packed [B, N, 3, H, d] tensor
@@ -237,14 +258,14 @@ const char* avion_last_hip_error(void) { return g_hip_error; }
 int avion_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int N, int d,
                    float scale, void* stream)
 {
-    return fwd_impl(q, k, v, o, lse, B, H, N, d, 1, false, scale, stream);
+    return fwd_impl(q, k, v, o, lse, B, H, N, d, 1, Variant{false, false}, scale, stream);
 }
 
 int avion_attn_fwd_qkvpacked(const void* qkv, void* o, float* lse, int B, int H, int N, int d, float scale, void* stream)
 {
     if (H < 1 || d < 1) return AVION_EINVAL;
     const Planes p(qkv, H, d);
-    return fwd_impl(p.q, p.k, p.v, o, lse, B, H, N, d, 3, false, scale, stream);
+    return fwd_impl(p.q, p.k, p.v, o, lse, B, H, N, d, 3, Variant{false, false}, scale, stream);
 }
 
 size_t avion_attn_bwd_workspace_bytes(int B, int H, int N, int d)
@@ -260,34 +281,51 @@ int avion_attn_bwd_dq(const void* q, const void* k, const void* v, const void* o
                       void* dq, int B, int H, int N, int d, float scale, void* workspace, size_t workspace_bytes,
                       void* stream)
 {
-    return dq_impl(q, k, v, o, lse, dO, dq, B, H, N, d, 1, false, scale, workspace, workspace_bytes, stream);
+    return dq_impl(q, k, v, o, lse, dO, dq, B, H, N, d, 1, Variant{false, false}, scale, workspace, workspace_bytes, stream);
 }
 
 int avion_attn_bwd_dkdv(const void* q, const void* k, const void* v, const float* lse, const void* dO, void* dk,
                         void* dv, int B, int H, int N, int d, float scale, const void* workspace,
                         size_t workspace_bytes, void* stream)
 {
-    return dkdv_impl(q, k, v, lse, dO, dk, dv, B, H, N, d, 1, false, scale, workspace, workspace_bytes, stream);
+    return dkdv_impl(q, k, v, lse, dO, dk, dv, B, H, N, d, 1, Variant{false, false}, scale, workspace, workspace_bytes,
+                     stream);
 }
 
 int avion_attn_bwd(const void* q, const void* k, const void* v, const void* o, const float* lse, const void* dO,
                    void* dq, void* dk, void* dv, int B, int H, int N, int d, float scale, void* workspace,
                    size_t workspace_bytes, void* stream)
 {
-    return bwd_impl(q, k, v, o, lse, dO, dq, dk, dv, B, H, N, d, false, scale, workspace, workspace_bytes, stream);
+    return bwd_impl(q, k, v, o, lse, dO, dq, dk, dv, B, H, N, d, Variant{false, false}, scale, workspace, workspace_bytes,
+                    stream);
+}
+
+int avion_attn_fwd_causal(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int N, int d,
+                          float scale, void* stream)
+{
+    return fwd_impl(q, k, v, o, lse, B, H, N, d, 1, Variant{false, true}, scale, stream);
+}
+
+int avion_attn_bwd_causal(const void* q, const void* k, const void* v, const void* o, const float* lse, const void* dO,
+                          void* dq, void* dk, void* dv, int B, int H, int N, int d, float scale, void* workspace,
+                          size_t workspace_bytes, void* stream)
+{
+    return bwd_impl(q, k, v, o, lse, dO, dq, dk, dv, B, H, N, d, Variant{false, true}, scale, workspace, workspace_bytes,
+                    stream);
 }
 
 int avion_attn_fwd_f16(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int N, int d,
                        float scale, void* stream)
 {
-    return fwd_impl(q, k, v, o, lse, B, H, N, d, 1, true, scale, stream);
+    return fwd_impl(q, k, v, o, lse, B, H, N, d, 1, Variant{true, false}, scale, stream);
 }
 
 int avion_attn_bwd_f16(const void* q, const void* k, const void* v, const void* o, const float* lse, const void* dO,
                        void* dq, void* dk, void* dv, int B, int H, int N, int d, float scale, void* workspace,
                        size_t workspace_bytes, void* stream)
 {
-    return bwd_impl(q, k, v, o, lse, dO, dq, dk, dv, B, H, N, d, true, scale, workspace, workspace_bytes, stream);
+    return bwd_impl(q, k, v, o, lse, dO, dq, dk, dv, B, H, N, d, Variant{true, false}, scale, workspace, workspace_bytes,
+                    stream);
 }
 
 int avion_attn_bwd_qkvpacked(const void* qkv, const void* o, const float* lse, const void* dO, void* dqkv, int B, int H,
@@ -302,10 +340,11 @@ int avion_attn_bwd_qkvpacked(const void* qkv, const void* o, const float* lse, c
     if (!workspace_ok(workspace, workspace_bytes, B, H, N, d)) return AVION_EWORKSPACE;
     const Planes in(qkv, H, d), out(dqkv, H, d);
     void *dq = const_cast<char*>(out.q), *dk = const_cast<char*>(out.k), *dv = const_cast<char*>(out.v);
-    const int rq = dq_impl(in.q, in.k, in.v, o, lse, dO, dq, B, H, N, d, 3, false, scale, workspace, workspace_bytes,
-                           stream);
+    const int rq = dq_impl(in.q, in.k, in.v, o, lse, dO, dq, B, H, N, d, 3, Variant{false, false}, scale, workspace,
+                           workspace_bytes, stream);
     if (rq != AVION_OK) return rq;
-    return dkdv_impl(in.q, in.k, in.v, lse, dO, dk, dv, B, H, N, d, 3, false, scale, workspace, workspace_bytes, stream);
+    return dkdv_impl(in.q, in.k, in.v, lse, dO, dk, dv, B, H, N, d, 3, Variant{false, false}, scale, workspace,
+                     workspace_bytes, stream);
 }
 
 }  // extern "C"

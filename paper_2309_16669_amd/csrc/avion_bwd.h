@@ -39,7 +39,7 @@ struct DqCfg {
     static constexpr int WAVES_PER_SIMD = D == 64 ? 3 : 2;  // LDS would allow more; registers do not
 };
 
-template <int D, int NW, typename E>
+template <int D, int NW, typename E, bool CAUSAL>
 __global__ void __launch_bounds__(NW * 64, (DqCfg<D, NW>::WAVES_PER_SIMD))
 avion_dq_kernel(const raw16* __restrict__ q, const raw16* __restrict__ k, const raw16* __restrict__ v,
                     const raw16* __restrict__ o, const raw16* __restrict__ dO, const float* __restrict__ lse,
@@ -65,7 +65,11 @@ avion_dq_kernel(const raw16* __restrict__ q, const raw16* __restrict__ k, const 
     const int q0 = qb * BM + wave * 32;
     const bool wave_active = q0 < N;
     const int tr_off = tr_lane_offset(lane, STRIDE);
-    const int ntiles = (N + BN - 1) / BN;
+    // keys seen by this lane's query, by any query of the wavefront, by all of them (see the forward)
+    const int key_limit = CAUSAL ? min(N, q0 + l32 + 1) : N;
+    const int wave_key_end = CAUSAL ? min(N, q0 + 32) : N;
+    const int mask_from = CAUSAL ? min(N, q0 + 1) : N;
+    const int ntiles = ((CAUSAL ? min(N, qb * BM + BM) : N) + BN - 1) / BN;
 
     const Ring ring(k + head_off, rs, v + head_off, rs, N, nullptr, 0, ntiles, smem, wave, lane);
     ring.fetch(0);
@@ -109,7 +113,7 @@ avion_dq_kernel(const raw16* __restrict__ q, const raw16* __restrict__ k, const 
     auto unit = [&](auto ragged, const char* kt, const char* vt, int hk, int key_base) {
         constexpr bool RAGGED = decltype(ragged)::value;
         f32x16 s, dp;
-        if constexpr (RAGGED) s = key_mask_block(key_base, g, N);
+        if constexpr (RAGGED) s = key_mask_block(key_base, g, key_limit);
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             const frag8 ak = nat_frag(kt, STRIDE, 32 * hk + l32, ks, g);
@@ -142,7 +146,8 @@ avion_dq_kernel(const raw16* __restrict__ q, const raw16* __restrict__ k, const 
 #pragma unroll
             for (int hk = 0; hk < 2; ++hk) {
                 const int key_base = t * BN + 32 * hk;
-                if (key_base + 32 > N) unit(std::true_type{}, ring.buf(t), ring.buf(t) + Ring::OFF_B, hk, key_base);
+                if (CAUSAL && key_base >= wave_key_end) continue;  // no query of this wavefront sees these keys
+                if (key_base + 32 > mask_from) unit(std::true_type{}, ring.buf(t), ring.buf(t) + Ring::OFF_B, hk, key_base);
                 else unit(std::false_type{}, ring.buf(t), ring.buf(t) + Ring::OFF_B, hk, key_base);
             }
         }
@@ -166,7 +171,7 @@ struct DkvCfg {
     static constexpr int WAVES_PER_SIMD = 2;  // a floor for the register budget; D = 64 fits three
 };
 
-template <int D, int NW, typename E>
+template <int D, int NW, typename E, bool CAUSAL>
 __global__ void __launch_bounds__(NW * 64, (DkvCfg<D, NW>::WAVES_PER_SIMD))
 avion_dkdv_kernel(const raw16* __restrict__ q, const raw16* __restrict__ k, const raw16* __restrict__ v,
                       const raw16* __restrict__ dO, const float* __restrict__ rowsc, raw16* __restrict__ dk,
@@ -196,9 +201,13 @@ avion_dkdv_kernel(const raw16* __restrict__ q, const raw16* __restrict__ k, cons
     const bool wave_active = k0 < N;
     const int tr_off = tr_lane_offset(lane, STRIDE);
 
+    // causal attention: the keys of this workgroup are seen by the queries from its first key on only,
+    // so the stream of query tiles starts there
+    const int t0 = CAUSAL ? kb * BNK / BQ : 0;
+
     const Ring ring(q + head_off, rs, dO + head_off_o, rs_o, N, rowsc + (long)bh * 2 * npad, npad, ntiles, smem, wave,
                     lane);
-    ring.fetch(0);
+    ring.fetch(t0);
 
     // K and V fragments (B operands: lane = key) stay in registers
     frag8 kf[KS], vf[KS];
@@ -217,14 +226,18 @@ avion_dkdv_kernel(const raw16* __restrict__ q, const raw16* __restrict__ k, cons
         dka[ct] = f32x16_zero();
         dva[ct] = f32x16_zero();
     }
-    Ring::landed_barrier();  // tile 0 is in LDS (and the fragments above have arrived)
+    Ring::landed_barrier();  // the first tile is in LDS (and the fragments above have arrived)
 
-    for (int t = 0; t < ntiles; ++t) {
+    for (int t = t0; t < ntiles; ++t) {
         ring.fetch(t + 1);  // into the buffer of tile t-1, which nobody reads any more
         if (wave_active) {
             const char* buf = ring.buf(t);
 #pragma unroll
             for (int hq = 0; hq < 2; ++hq) {
+                const int query_base = t * BQ + 32 * hq;
+                // causal: units whose queries all lie before this wavefront's keys contribute nothing;
+                // units that straddle the diagonal start their scores from the mask
+                if (CAUSAL && query_base + 32 <= k0) continue;
                 const float* rowv = reinterpret_cast<const float*>(buf + OFF_ROW) + 32 * hq + 4 * g;
                 // dP starts from -delta of the accumulator rows' queries (broadcast LDS reads)
                 f32x16 s, dp;
@@ -234,11 +247,15 @@ avion_dkdv_kernel(const raw16* __restrict__ q, const raw16* __restrict__ k, cons
 #pragma unroll
                     for (int e = 0; e < 4; ++e) dp[4 * a4 + e] = d4[e];
                 }
+                if constexpr (CAUSAL) {
+                    if (query_base < k0 + 31) s = query_mask_block(query_base, g, k0 + l32);
+                    else s = f32x16_zero();
+                }
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
                     const frag8 aq = nat_frag(buf, STRIDE, 32 * hq + l32, ks, g);
                     const frag8 ag = nat_frag(buf + OFF_G, STRIDE, 32 * hq + l32, ks, g);
-                    s = E::mfma(aq, kf[ks], ks == 0 ? f32x16_zero() : s);
+                    s = E::mfma(aq, kf[ks], ks == 0 && !CAUSAL ? f32x16_zero() : s);
                     dp = E::mfma(ag, vf[ks], dp);
                 }
                 f32x4 l4[4];

@@ -342,6 +342,17 @@ DEVINL f32x16 key_mask_block(int key_base, int g, int N)
     for (int i = 0; i < 16; ++i) r[i] = key_base + 8 * (i / 4) + 4 * g + (i % 4) < N ? 0.f : -1.0e30f;
     return r;
 }
+// Causal attention (query i sees keys 0..i): the same with a per-lane bound.  In the query-stationary
+// kernels the lane is a query and passes N = min(N, query + 1) to key_mask_block above.  In the
+// key-stationary kernel the lane is a key and the registers are queries
+// query_base + 8*(i/4) + 4*g + i%4: a query below the lane's key must not see it.
+DEVINL f32x16 query_mask_block(int query_base, int g, int key)
+{
+    f32x16 r;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) r[i] = query_base + 8 * (i / 4) + 4 * g + (i % 4) >= key ? 0.f : -1.0e30f;
+    return r;
+}
 
 // ---------------------------------------------------------------------------------------------
 // Ring of NBUF buffers in LDS, each holding an A tile and a B tile of 64 token rows in the padded

@@ -48,10 +48,11 @@ struct FwdCfg {
 // Classic online softmax with a running maximum, one 64-key tile at a time, staged through
 // registers into the ring's two buffers.  Used only as the fallback described above; same register
 // layouts as the main loop.
+// key_limit: this lane's query sees keys below it (N, or query + 1 for causal attention).
 template <int D, int NW, typename E>
 DEVINL void avion_fwd_safe_pass(char* smem, const SliceView& kh, const SliceView& vh, const frag8 (&qf)[D / 16],
                                 f32x16 (&oacc)[(D + 31) / 32], float& m_used, float& lsum, float& rsum, int N,
-                                float cs, bool wave_active, int tid, int l32, int g, int tr_off)
+                                int key_limit, float cs, bool wave_active, int tid, int l32, int g, int tr_off)
 {
     using Cfg = FwdCfg<D, NW>;
     using Stage = typename Cfg::Stage;
@@ -92,13 +93,13 @@ DEVINL void avion_fwd_safe_pass(char* smem, const SliceView& kh, const SliceView
                 for (int ks = 0; ks < KS; ++ks)
                     s = E::mfma(nat_frag(kc, STRIDE, 32 * kt + l32, ks, g), qf[ks], ks == 0 ? f32x16_zero() : s);
                 const int key0 = t * BN + 32 * kt + 4 * g;
-                if (key0 + 28 >= N) {
+                if (key0 + 28 >= key_limit) {
 #pragma unroll
                     for (int i = 0; i < 16; ++i)
-                        if (key0 + 8 * (i / 4) + (i % 4) >= N) s[i] = -INFINITY;
+                        if (key0 + 8 * (i / 4) + (i % 4) >= key_limit) s[i] = -INFINITY;
                 }
                 const float m2 = both_halves_max(max16(s)) * cs;
-                const float mn = fmaxf(m_used, m2);  // finite: key 0 exists for every query
+                const float mn = fmaxf(m_used, m2);  // finite: key 0 is seen by every query
                 const float alpha = fast_exp2(m_used - mn);
                 m_used = mn;
                 lsum *= alpha;
@@ -132,8 +133,10 @@ DEVINL void avion_fwd_safe_pass(char* smem, const SliceView& kh, const SliceView
     }
 }
 
-template <int D, int NW, typename E>
-__global__ void __launch_bounds__(NW * 64, (FwdCfg<D, NW>::WAVES_PER_SIMD))
+// (The causal instance carries a per-lane key bound and a few more scalars: it is sized for one
+// wavefront per SIMD less than the register file would otherwise hold, which keeps it free of spills.)
+template <int D, int NW, typename E, bool CAUSAL>
+__global__ void __launch_bounds__(NW * 64, (FwdCfg<D, NW>::WAVES_PER_SIMD - (CAUSAL && FwdCfg<D, NW>::WAVES_PER_SIMD > 3 ? 1 : 0)))
 avion_fwd_kernel(const raw16* __restrict__ q, const raw16* __restrict__ k, const raw16* __restrict__ v,
                  raw16* __restrict__ o, float* __restrict__ lse, int H, int N, int rs_qkv, int rs_o, int nqb, int nblocks,
                  float cs)
@@ -160,7 +163,13 @@ avion_fwd_kernel(const raw16* __restrict__ q, const raw16* __restrict__ k, const
     const int q0 = qb * BM + wave * 32;  // first query of this wavefront
     const bool wave_active = q0 < N;
     const int tr_off = tr_lane_offset(lane, STRIDE);
-    const int ntiles = (N + BN - 1) / BN;
+    // Keys this lane's query sees: all N, or 0..query for causal attention.  For the whole wavefront:
+    // units that start at or beyond wave_key_end are skipped, units that reach beyond mask_from start
+    // their scores from the mask; the workgroup streams the tiles up to its last query only.
+    const int key_limit = CAUSAL ? min(N, q0 + l32 + 1) : N;
+    const int wave_key_end = CAUSAL ? min(N, q0 + 32) : N;
+    const int mask_from = CAUSAL ? min(N, q0 + 1) : N;
+    const int ntiles = ((CAUSAL ? min(N, qb * BM + BM) : N) + BN - 1) / BN;
 
     const Ring ring(k + head_off, rs, v + head_off, rs, N, nullptr, 0, ntiles, smem, wave, lane);
     ring.fetch(0);
@@ -185,7 +194,7 @@ avion_fwd_kernel(const raw16* __restrict__ q, const raw16* __restrict__ k, const
     auto scores = [&](auto ragged, const char* kt, int hk, int key_base) -> f32x16 {
         constexpr bool RAGGED = decltype(ragged)::value;
         f32x16 s;
-        if constexpr (RAGGED) s = key_mask_block(key_base, g, N);
+        if constexpr (RAGGED) s = key_mask_block(key_base, g, key_limit);
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
             s = E::mfma(nat_frag(kt, STRIDE, 32 * hk + l32, ks, g), qf[ks], ks == 0 && !RAGGED ? f32x16_zero() : s);
@@ -202,8 +211,9 @@ avion_fwd_kernel(const raw16* __restrict__ q, const raw16* __restrict__ k, const
 #pragma unroll
             for (int hk = 0; hk < 2; ++hk) {
                 const int key_base = t * BN + 32 * hk;
+                if (CAUSAL && key_base >= wave_key_end) continue;  // no query of this wavefront sees these keys
                 f32x16 s;
-                if (key_base + 32 > N) s = scores(std::true_type{}, kt, hk, key_base);
+                if (key_base + 32 > mask_from) s = scores(std::true_type{}, kt, hk, key_base);
                 else s = scores(std::false_type{}, kt, hk, key_base);
                 // the V^T operands are requested before the vector work so that they are there after it
                 frag8 vf[2][CT];
@@ -238,7 +248,8 @@ avion_fwd_kernel(const raw16* __restrict__ q, const raw16* __restrict__ k, const
     bool bad = false;
     if (wave_active) bad = !(both_halves_sum(lsum) <= E::kRowSumLimit);
     if (__syncthreads_or(bad ? 1 : 0))
-        avion_fwd_safe_pass<D, NW, E>(smem, kh, vh, qf, oacc, m_used, lsum, rsum, N, cs, wave_active, tid, l32, g, tr_off);
+        avion_fwd_safe_pass<D, NW, E>(smem, kh, vh, qf, oacc, m_used, lsum, rsum, N, key_limit, cs, wave_active, tid, l32, g,
+                                      tr_off);
 
     // every wavefront is past its last tile read (barrier above): the tile buffers are free and
     // serve as the per-wavefront staging area of the output rows

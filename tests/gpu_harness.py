@@ -26,18 +26,20 @@ def bf16_tensor_to_f64(t):
     return si.bf16_bits_to_f64(bits)
 
 
-def run_hip(w, x, poison=True):
-    """fwd + bwd of workload w on the GPU through the C ABI. Returns torch tensors."""
+def run_hip(w, x, poison=True, causal=False):
+    """fwd + bwd of workload w on the GPU through the C ABI (the causal entry points if asked).
+    Returns torch tensors."""
     import torch
     import paper_2309_16669_amd as av
+    attn_fwd, attn_bwd = (av.attn_fwd_causal, av.attn_bwd_causal) if causal else (av.attn_fwd, av.attn_bwd)
     q, k, v, dO = (to_gpu_bf16(x[n]) for n in ("q", "k", "v", "dO"))
     fill = float("nan") if poison else 0.0
     o = torch.full_like(q, fill)
     lse = torch.full((w.B, w.H, w.N), fill, dtype=torch.float32, device="cuda")
     dq, dk, dv = (torch.full_like(q, fill) for _ in range(3))
     ws = torch.empty(av.attn_bwd_workspace_bytes(w.B, w.H, w.N, w.d), dtype=torch.uint8, device="cuda")
-    av.attn_fwd(q, k, v, o, lse, w.scale)
-    av.attn_bwd(q, k, v, o, lse, dO, dq, dk, dv, w.scale, ws)
+    attn_fwd(q, k, v, o, lse, w.scale)
+    attn_bwd(q, k, v, o, lse, dO, dq, dk, dv, w.scale, ws)
     torch.cuda.synchronize()
     return dict(o=o, lse=lse, dq=dq, dk=dk, dv=dv)
 
@@ -59,6 +61,32 @@ def run_hip_packed(w, x, poison=True):
     av.attn_bwd_qkvpacked(qkv, o, lse, dO, dqkv, w.scale, ws)
     torch.cuda.synchronize()
     return dict(o=o, lse=lse, dq=dqkv[:, :, 0], dk=dqkv[:, :, 1], dv=dqkv[:, :, 2])
+
+
+def check_causal_against_oracle(w, x, out, slices=None):
+    """Causal results against the causal oracle, at the bounds of the unmasked operation.  Row i of a
+    causal problem is an attention over i+1 keys: its first rows carry weights near one, so dV and dK
+    of the first keys reach magnitudes of 4 and more, where half a bf16 ulp alone is 1.6e-2; the
+    absolute bound therefore follows one bf16 ulp of the largest reference value (as for the other
+    near one-hot stress cases), the relative bound is unchanged."""
+    import oracle
+    report = {}
+    tol = REL_FRO if w.N >= 16 else REL_FRO_TINY_N
+    sls = [(slice(None),) * 3] if slices is None else [(slice(b, b + 1), slice(None), slice(h, h + 1)) for b, h in slices]
+    for n_sl, sl in enumerate(sls):
+        ro, rl = oracle.fwd(x["q"][sl], x["k"][sl], x["v"][sl], w.scale, causal=True)
+        rdq, rdk, rdv = oracle.bwd(x["q"][sl], x["k"][sl], x["v"][sl], x["dO"][sl], w.scale, causal=True)
+        tag = "" if slices is None else f"[b={slices[n_sl][0]},h={slices[n_sl][1]}]"
+        lse_gpu = out["lse"].double().cpu().numpy()
+        if slices is not None:
+            b, h = slices[n_sl]
+            lse_gpu = lse_gpu[b:b + 1, h:h + 1]
+        lse_err = float(np.abs(lse_gpu - rl).max())
+        report["LSE" + tag] = (lse_err, 0.0)
+        assert lse_err <= LSE_ABS, f"LSE{tag}: max-abs error {lse_err:.3e} > {LSE_ABS}"
+        for name, key, ref in (("O", "o", ro), ("dQ", "dq", rdq), ("dK", "dk", rdk), ("dV", "dv", rdv)):
+            assert_close(name + tag, bf16_tensor_to_f64(out[key][sl]), ref, report, tol, strict_abs=False)
+    return report
 
 
 # fp16 variant: unit roundoff 2^-11 instead of 2^-8, so the same error sources (rounding of P, dS
@@ -138,14 +166,14 @@ def assert_close(name, gpu_f64, ref, report=None, rel_tol=REL_FRO, strict_abs=Tr
     assert rel <= rel_tol, f"{name}: relative Frobenius error {rel:.3e} > {rel_tol}"
 
 
-def check_against_oracle(w, x, out, slices=None, strict_abs=True):
+def check_against_oracle(w, x, out, slices=None, strict_abs=True, causal=False):
     """Compare the HIP results with the oracle, on the whole problem or on chosen (b,h) slices."""
     import oracle
     report = {}
     grad_tol = REL_FRO if w.N >= 16 else REL_FRO_TINY_N
     if slices is None:
-        ro, rl = oracle.fwd(x["q"], x["k"], x["v"], w.scale)
-        rdq, rdk, rdv = oracle.bwd(x["q"], x["k"], x["v"], x["dO"], w.scale)
+        ro, rl = oracle.fwd(x["q"], x["k"], x["v"], w.scale, causal=causal)
+        rdq, rdk, rdv = oracle.bwd(x["q"], x["k"], x["v"], x["dO"], w.scale, causal=causal)
         assert_close("O", bf16_tensor_to_f64(out["o"]), ro, report, REL_FRO, strict_abs)
         lse_err = float(np.abs(out["lse"].double().cpu().numpy() - rl).max())
         report["LSE"] = (lse_err, 0.0)
@@ -156,8 +184,8 @@ def check_against_oracle(w, x, out, slices=None, strict_abs=True):
         return report
     for (b, h) in slices:
         sl = (slice(b, b + 1), slice(None), slice(h, h + 1))
-        ro, rl = oracle.fwd(x["q"][sl], x["k"][sl], x["v"][sl], w.scale)
-        rdq, rdk, rdv = oracle.bwd(x["q"][sl], x["k"][sl], x["v"][sl], x["dO"][sl], w.scale)
+        ro, rl = oracle.fwd(x["q"][sl], x["k"][sl], x["v"][sl], w.scale, causal=causal)
+        rdq, rdk, rdv = oracle.bwd(x["q"][sl], x["k"][sl], x["v"][sl], x["dO"][sl], w.scale, causal=causal)
         tag = f"[b={b},h={h}]"
         assert_close("O" + tag, bf16_tensor_to_f64(out["o"][sl]), ro, report, REL_FRO, strict_abs)
         lse_err = float(np.abs(out["lse"][b, h].double().cpu().numpy() - rl[0, 0]).max())
