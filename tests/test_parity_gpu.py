@@ -243,6 +243,71 @@ def test_scores_far_above_the_first_keys_take_the_running_max_path():
         assert np.abs(lse - rl).max() <= 2e-6 * np.abs(rl).max() + 1e-3  # fp32 LSE of magnitude ~1e3
 
 
+def test_largest_addressable_head_slice():
+    # The kernels address one (batch, head) slice with 32-bit byte offsets and the library accepts
+    # shapes up to (N + 256) * H*d*2 < 2^31.  H = 4000, N = 3900 is just inside (2.128e9); the last
+    # head's last rows sit at the far end of that range.  Inputs are drawn on the GPU (seeded); the
+    # oracle gets the bytes of the sampled heads copied back.
+    import torch
+    import oracle
+    import paper_2309_16669_amd as av
+    B, H, N, d = 1, 4000, 3900, 64
+    assert (N + 256) * H * d * 2 < 2 ** 31 <= (N + 64 + 256) * H * d * 2
+    g = torch.Generator(device="cuda")
+    g.manual_seed(20230916)
+    q, k, v, dO = (torch.randn((B, N, H, d), device="cuda", generator=g, dtype=torch.float32).to(torch.bfloat16)
+                   for _ in range(4))
+    o = torch.full_like(q, float("nan"))
+    lse = torch.full((B, H, N), float("nan"), dtype=torch.float32, device="cuda")
+    dq, dk, dv = (torch.full_like(q, float("nan")) for _ in range(3))
+    ws = torch.empty(av.attn_bwd_workspace_bytes(B, H, N, d), dtype=torch.uint8, device="cuda")
+    av.attn_fwd(q, k, v, o, lse, 0.125)
+    av.attn_bwd(q, k, v, o, lse, dO, dq, dk, dv, 0.125, ws)
+    torch.cuda.synchronize()
+    bits = lambda t, h: t[:, :, h:h + 1].contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+    for h in (0, 1777, H - 1):
+        ro, rl = oracle.fwd(bits(q, h), bits(k, h), bits(v, h), 0.125)
+        rdq, rdk, rdv = oracle.bwd(bits(q, h), bits(k, h), bits(v, h), bits(dO, h), 0.125)
+        assert np.abs(lse[:, h:h + 1].double().cpu().numpy() - rl).max() <= gh.LSE_ABS
+        for name, t, ref in (("O", o, ro), ("dQ", dq, rdq), ("dK", dk, rdk), ("dV", dv, rdv)):
+            gh.assert_close(f"{name}[h={h}]", si.bf16_bits_to_f64(bits(t, h)), ref)
+    # every element was written (the buffers were filled with NaN)
+    for t in (o, dq, dk, dv, lse):
+        assert bool(torch.isfinite(t.float()).all())
+    # one tile further is refused before anything is launched
+    assert av.load_library().avion_attn_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(),
+                                            B, H, N + 64, d, __import__("ctypes").c_float(0.125), None) == av.EUNSUPPORTED
+
+
+def test_two_streams_with_their_own_workspaces_do_not_disturb_each_other():
+    # calls only enqueue on the caller's stream: two problems in flight on two streams, each with its
+    # own workspace, give the same bits as when run one after the other on the default stream
+    import torch
+    import paper_2309_16669_amd as av
+    ws_ = [si.small_workload(2, 4, 700, 64, seed=91), si.small_workload(1, 6, 1100, 64, seed=92)]
+    xs = [si.make_inputs(w) for w in ws_]
+    ref = [gh.run_hip(w, x) for w, x in zip(ws_, xs)]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    outs = []
+    for w, x, st in zip(ws_, xs, streams):
+        q, k, v, dO = (gh.to_gpu_bf16(x[n]) for n in ("q", "k", "v", "dO"))
+        o = torch.empty_like(q)
+        lse = torch.empty((w.B, w.H, w.N), dtype=torch.float32, device="cuda")
+        dq, dk, dv = (torch.empty_like(q) for _ in range(3))
+        wsb = torch.empty(av.attn_bwd_workspace_bytes(w.B, w.H, w.N, w.d), dtype=torch.uint8, device="cuda")
+        outs.append(dict(q=q, k=k, v=v, dO=dO, o=o, lse=lse, dq=dq, dk=dk, dv=dv, ws=wsb))
+    torch.cuda.synchronize()
+    for rep in range(3):          # interleave the enqueues
+        for w, t, st in zip(ws_, outs, streams):
+            av.attn_fwd(t["q"], t["k"], t["v"], t["o"], t["lse"], w.scale, st)
+            av.attn_bwd(t["q"], t["k"], t["v"], t["o"], t["lse"], t["dO"], t["dq"], t["dk"], t["dv"], w.scale, t["ws"], st)
+    torch.cuda.synchronize()
+    for r, t in zip(ref, outs):
+        for n in ("o", "dq", "dk", "dv"):
+            assert torch.equal(r[n].view(torch.int16), t[n].view(torch.int16)), n
+        assert torch.equal(r["lse"], t["lse"])
+
+
 def test_bad_arguments_raise_on_gpu_tensors():
     import torch
     import paper_2309_16669_amd as av
