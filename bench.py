@@ -29,9 +29,9 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published figure
 # known size); filled in from the summaries under profiles/ -- None until measured.
 MEASURED_HBM_BYTES_PER_LAUNCH = {
     # profiles/hbm_traffic_vitb_batch.txt: FETCH_SIZE x 2.0 (copy-kernel factor) + WRITE_SIZE x 1.0
-    ("vitb_batch", "avion_fwd_kernel"): 311.8e6,
-    ("vitb_batch", "avion_dq_kernel"): 472.6e6,
-    ("vitb_batch", "avion_dkdv_kernel"): 471.1e6,
+    ("vitb_batch", "avion_fwd_kernel"): 312.0e6,
+    ("vitb_batch", "avion_dq_kernel"): 473.1e6,
+    ("vitb_batch", "avion_dkdv_kernel"): 471.3e6,
 }
 
 
