@@ -92,6 +92,10 @@ def main():
     ap.add_argument("--layout", choices=("separate", "packed"), default="separate",
                     help="separate = q, k, v as three [B,N,H,d] tensors (the reported configuration); packed = one "
                          "[B,N,3,H,d] tensor through the *_qkvpacked entry points (same kernels, token stride 3*H*d)")
+    ap.add_argument("--checkpointing", action="store_true",
+                    help="also time the step of a layer trained with gradient checkpointing (Sec. 4.1 of the "
+                         "paper): the forward runs a second time before the backward; reported beside the "
+                         "metric, which is unchanged")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain device copy of Q (known size) so that HBM counters of a "
                          "rocprofv3 --pmc run can be scaled")
@@ -227,6 +231,16 @@ def main():
                      "algorithmic_flops_per_launch": dom_flops, "avg_launch_ms": dom_ms},
     }
     out["roofline"]["traffic"] = MEASURED_HBM_BYTES_PER_LAUNCH.get((args.workload, dom_name))
+    if args.checkpointing:
+        def ckpt_step():
+            fwd()      # forward pass of the training step (activations dropped)
+            fwd()      # recomputation of the layer inside the backward pass
+            bwd()
+        ms_ckpt = timed(ckpt_step, args.steps, 2, stream)
+        out["gradient_checkpointing"] = {
+            "ms_per_step": ms_ckpt, "slowdown_vs_plain_step": ms_ckpt / ms_step,
+            "note": "fwd + fwd + bwd; still 14*B*H*N^2*d useful flops",
+            "tflops_useful": tf(14 * base, ms_ckpt)}
     if not args.no_cpu_baseline and not f16:
         log(f"[bench] timing the CPU oracle on {args.cpu_clips} clips ...")
         out["cpu_baseline"] = cpu_baseline(w, x, min(args.cpu_clips, w.B))
