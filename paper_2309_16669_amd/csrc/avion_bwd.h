@@ -23,6 +23,11 @@
 // and several resident wavefronts per SIMD fill each other's waits.  Tiles stream through two LDS
 // buffers filled by LDS-direct loads; one workgroup barrier per 64-row tile certifies that the next
 // tile has landed and that the previous one is no longer read, so that its buffer can be refilled.
+//
+// Template parameters of both kernels: head dim D, wavefronts per workgroup NW, element format E
+// (Bf16 or F16: contraction instruction and roundings), CAUSAL (query i sees keys 0..i: units that
+// no (query, key) pair of a wavefront needs are skipped, units on the diagonal start their score
+// accumulator from a mask of 0 / -1e30, whose weights come out as exactly 0).
 #pragma once
 #include "avion_common.h"
 

@@ -12,7 +12,7 @@
 // rows (8 consecutive channels per lane), and operands whose contraction index is a token are read
 // from a transposed LDS tile whose token positions are permuted to match the accumulator rows.
 //
-// LDS tile: R token rows of D bf16 in their natural order, row stride D*2+16 bytes for D = 64 and
+// LDS tile: R token rows of D two-byte elements in their natural order, row stride D*2+16 bytes for D = 64 and
 // D*2+48 for D = 80 (an odd multiple of 16 bytes, so the 16-byte fragment reads of 16 consecutive
 // lanes hit distinct banks; for D = 80 the zeroed pad also covers the reads of the channel tile
 // that reaches past channel 79).
@@ -449,7 +449,7 @@ DEVINL int xcd_local_id(int block, int nblocks)
 // Epilogue store of one wavefront's 32 x D result tile held as transposed accumulators
 // (lane = token row l32 of the tile, register v of channel tile ct = channel
 // 32*ct + 8*(v/4) + 4*g + v%4).  Written straight from that layout every lane would store 8-byte
-// pieces of 32 different rows; instead the tile is rounded to bf16, laid out row-major in a
+// pieces of 32 different rows; instead the tile is rounded to the element format, laid out row-major in a
 // per-wavefront LDS region and read back so that 8 (D=64) or 10 (D=80) consecutive lanes store one
 // full row with 16-byte pieces.  `region` must not be in use by any other wavefront; LDS
 // operations of one wavefront execute in order, so no barrier is needed in between.

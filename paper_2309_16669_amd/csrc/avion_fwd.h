@@ -28,6 +28,10 @@
 // must stay below 65504).  That is detected from the final row sum against E::kRowSumLimit
 // (workgroup-wide), and the whole workgroup then recomputes its rows with the classic running
 // maximum (avion_fwd_safe_pass).  Random or trained activations never get there.
+//
+// Template parameters: head dim D, wavefronts per workgroup NW, element format E (Bf16 or F16),
+// CAUSAL (query i sees keys 0..i; the reference m is then the maximum over the visible ones of the
+// first 32 keys -- key 0 is visible to every query).
 #pragma once
 #include "avion_common.h"
 
