@@ -142,6 +142,31 @@ def test_causal_text_encoder_batch_on_sampled_heads():
     assert torch.equal(out["o"][:, 0].view(torch.int16), gh.to_gpu_bf16(x["v"])[:, 0].view(torch.int16))
 
 
+def test_causal_running_max_path():
+    # as test_scores_far_above_the_first_keys_take_the_running_max_path, with the causal mask: keys
+    # from 64 on are 16 times larger and scale = 1, so rows from 64 on overflow the fixed reference
+    # and the workgroup redoes its rows with a running maximum -- which must honour the mask too
+    import oracle
+    import paper_2309_16669_amd as av
+    import torch
+    for d in (64, 80):
+        w = si.small_workload(1, 2, 200, d, seed=4321 + d, scale=1.0)
+        x = si.make_inputs(w)
+        big = si.bf16_bits_to_f32(x["k"][:, 64:]) * np.float32(16.0)
+        x["k"][:, 64:] = si.f32_to_bf16_bits(big)          # exact: power of two
+        q, k, v = (gh.to_gpu_bf16(x[n]) for n in ("q", "k", "v"))
+        o = torch.full_like(q, float("nan"))
+        lse = torch.full((w.B, w.H, w.N), float("nan"), dtype=torch.float32, device="cuda")
+        av.attn_fwd_causal(q, k, v, o, lse, w.scale)
+        torch.cuda.synchronize()
+        ro, rl = oracle.fwd(x["q"], x["k"], x["v"], w.scale, causal=True)
+        og = gh.bf16_tensor_to_f64(o)
+        lg = lse.double().cpu().numpy()
+        assert np.all(np.isfinite(og)) and np.all(np.isfinite(lg))
+        assert np.abs(og - ro).max() <= 2.0 ** -7 * np.abs(ro).max()
+        assert np.abs(lg - rl).max() <= 2e-6 * np.abs(rl).max() + 1e-3
+
+
 F16_SHAPES = [(1, 1, 1, 64), (1, 2, 33, 64), (2, 3, 197, 64), (1, 2, 300, 64), (1, 2, 785, 64), (1, 1, 1569, 64),
               (1, 1, 1, 80), (2, 2, 300, 80), (1, 1, 785, 80)]
 
