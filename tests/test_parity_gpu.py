@@ -333,6 +333,47 @@ def test_two_streams_with_their_own_workspaces_do_not_disturb_each_other():
         assert torch.equal(r["lse"], t["lse"])
 
 
+def test_autograd_front_end_matches_oracle_gradients():
+    # loss = sum(O * W) through torch.autograd: the gradients that reach q, k, v are the library's
+    # backward for dO = W; unmasked, causal, fp16 and packed forms
+    import torch
+    import oracle
+    from paper_2309_16669_amd import autograd as ag
+    w = si.small_workload(2, 3, 210, 64, seed=606)
+    x = si.make_inputs(w)
+    dO = gh.to_gpu_bf16(x["dO"])
+    for causal in (False, True):
+        q, k, v = (gh.to_gpu_bf16(x[n]).requires_grad_() for n in ("q", "k", "v"))
+        o = ag.attention(q, k, v, w.scale, causal=causal)
+        (o.float() * dO.float()).sum().backward()
+        out = dict(o=o.detach(), dq=q.grad, dk=k.grad, dv=v.grad)
+        ro, _ = oracle.fwd(x["q"], x["k"], x["v"], w.scale, causal=causal)
+        refs = oracle.bwd(x["q"], x["k"], x["v"], x["dO"], w.scale, causal=causal)
+        gh.assert_close("O", gh.bf16_tensor_to_f64(out["o"]), ro, strict_abs=not causal)
+        for n, ref in zip(("dq", "dk", "dv"), refs):
+            gh.assert_close(n, gh.bf16_tensor_to_f64(out[n]), ref, strict_abs=not causal)
+    # packed: bit-identical to the unpacked gradients
+    qkv = gh.to_gpu_bf16(np.stack([x["q"], x["k"], x["v"]], axis=2)).requires_grad_()
+    o = ag.attention_qkvpacked(qkv, w.scale)
+    (o.float() * dO.float()).sum().backward()
+    q, k, v = (gh.to_gpu_bf16(x[n]).requires_grad_() for n in ("q", "k", "v"))
+    (ag.attention(q, k, v, w.scale).float() * dO.float()).sum().backward()
+    for i, t in enumerate((q, k, v)):
+        assert torch.equal(qkv.grad[:, :, i].contiguous().view(torch.int16), t.grad.view(torch.int16))
+    # fp16
+    x16 = si.make_inputs(w, fmt="f16")
+    up = lambda b: torch.from_numpy(np.ascontiguousarray(b).view(np.int16)).cuda().view(torch.float16)
+    q, k, v = (up(x16[n]).requires_grad_() for n in ("q", "k", "v"))
+    o = ag.attention(q, k, v, w.scale)
+    (o.float() * up(x16["dO"]).float()).sum().backward()
+    f = {n: si.f16_bits_to_f64(x16[n]) for n in x16}
+    ro, _ = oracle.fwd_f64(f["q"], f["k"], f["v"], w.scale)
+    refs = oracle.bwd_f64(f["q"], f["k"], f["v"], f["dO"], w.scale)
+    for n, got, ref in (("O", o.detach(), ro), ("dQ", q.grad, refs[0]), ("dK", k.grad, refs[1]), ("dV", v.grad, refs[2])):
+        max_abs, rel = gh.errors(got.double().cpu().numpy(), ref)
+        assert max_abs <= gh.MAX_ABS_F16 and rel <= gh.REL_FRO_F16, (n, max_abs, rel)
+
+
 def test_bad_arguments_raise_on_gpu_tensors():
     import torch
     import paper_2309_16669_amd as av
