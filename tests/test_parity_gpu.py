@@ -273,6 +273,7 @@ def test_largest_addressable_head_slice():
     # shapes up to (N + 256) * H*d*2 < 2^31.  H = 4000, N = 3900 is just inside (2.128e9); the last
     # head's last rows sit at the far end of that range.  Inputs are drawn on the GPU (seeded); the
     # oracle gets the bytes of the sampled heads copied back.
+    import ctypes
     import torch
     import oracle
     import paper_2309_16669_amd as av
@@ -301,7 +302,7 @@ def test_largest_addressable_head_slice():
         assert bool(torch.isfinite(t.float()).all())
     # one tile further is refused before anything is launched
     assert av.load_library().avion_attn_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(),
-                                            B, H, N + 64, d, __import__("ctypes").c_float(0.125), None) == av.EUNSUPPORTED
+                                            B, H, N + 64, d, ctypes.c_float(0.125), None) == av.EUNSUPPORTED
 
 
 def test_two_streams_with_their_own_workspaces_do_not_disturb_each_other():
