@@ -375,6 +375,40 @@ def test_autograd_front_end_matches_oracle_gradients():
         assert max_abs <= gh.MAX_ABS_F16 and rel <= gh.REL_FRO_F16, (n, max_abs, rel)
 
 
+def test_calls_can_be_captured_in_a_graph_and_replayed():
+    # the entry points only enqueue kernels on the caller's stream (no allocation, no memset, no
+    # synchronisation), so a forward + backward can be recorded into a HIP graph; every replay, with
+    # eager work and synchronisations in between and fresh inputs copied into the captured buffers,
+    # must give the bits of the eager call
+    import torch
+    import paper_2309_16669_amd as av
+    w = si.small_workload(2, 3, 450, 64, seed=808)
+    xs = [si.make_inputs(si.small_workload(2, 3, 450, 64, seed=808 + i)) for i in range(3)]
+    refs = [gh.run_hip(w, x) for x in xs]                      # eager; also warms up the library
+    q, k, v, dO = (gh.to_gpu_bf16(xs[0][n]).clone() for n in ("q", "k", "v", "dO"))
+    o = torch.empty_like(q)
+    lse = torch.empty((w.B, w.H, w.N), dtype=torch.float32, device="cuda")
+    dq, dk, dv = (torch.empty_like(q) for _ in range(3))
+    ws = torch.empty(av.attn_bwd_workspace_bytes(w.B, w.H, w.N, w.d), dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):                              # captures on a side stream
+        av.attn_fwd(q, k, v, o, lse, w.scale)
+        av.attn_bwd(q, k, v, o, lse, dO, dq, dk, dv, w.scale, ws)
+    for i in (1, 2, 0, 1):
+        for t, n in ((q, "q"), (k, "k"), (v, "v"), (dO, "dO")):
+            t.copy_(gh.to_gpu_bf16(xs[i][n]))
+        for t in (o, dq, dk, dv):
+            t.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for n, t in (("o", o), ("dq", dq), ("dk", dk), ("dv", dv)):
+            assert torch.equal(refs[i][n].view(torch.int16), t.view(torch.int16)), (i, n)
+        assert torch.equal(refs[i]["lse"], lse), i
+        gh.run_hip(w, xs[(i + 1) % 3])                         # unrelated eager work between replays
+
+
 def test_bad_arguments_raise_on_gpu_tensors():
     import torch
     import paper_2309_16669_amd as av
