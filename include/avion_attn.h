@@ -91,8 +91,9 @@ int avion_attn_bwd(const void *q, const void *k, const void *v, const void *o, c
 
 /*
  * The two phases of avion_attn_bwd, callable on their own (same argument rules as above).
- * avion_attn_bwd(...) is exactly avion_attn_bwd_dq(...) followed by avion_attn_bwd_dkdv(...) on
- * the same stream with the same workspace.
+ * avion_attn_bwd(...) gives exactly the bits of avion_attn_bwd_dq(...) followed by
+ * avion_attn_bwd_dkdv(...) on the same stream with the same workspace; for N <= 128 it runs both
+ * phases in one launch (one workgroup then covers a whole (batch, head)), otherwise as two.
  *
  *   avion_attn_bwd_dq   : query-stationary pass.  Computes the row sums delta = rowsum(dO o O) and
  *                         dQ = scale * (P o (dO V^T - delta)) K.  Writes dq (fully) and leaves

@@ -115,6 +115,23 @@ int launch_dkdv(const raw16* q, const raw16* k, const raw16* v, const raw16* dO,
     return e == hipSuccess ? AVION_OK : hip_fail(e, "launch avion_dkdv_kernel");
 }
 
+template <int D, int NW, typename E, bool CAUSAL>
+int launch_bwd_small(const raw16* q, const raw16* k, const raw16* v, const raw16* o, const raw16* dO, const float* lse,
+                     raw16* dq, raw16* dk, raw16* dv, float* rowsc, int B, int H, int N, Strides rs, float scale,
+                     hipStream_t st)
+{
+    using Cfg = BwdSmallCfg<D, NW>;
+    static hipError_t attr = allow_lds(avion_bwd_small_kernel<D, NW, E, CAUSAL>, Cfg::LDS_BYTES);
+    if (attr != hipSuccess) return hip_fail(attr, "hipFuncSetAttribute(bwd_small)");
+    const long long nblocks = (long long)B * H;
+    unsigned grid;
+    if (!grid_for(nblocks, &grid)) return AVION_EUNSUPPORTED;
+    hipLaunchKernelGGL((avion_bwd_small_kernel<D, NW, E, CAUSAL>), dim3(grid), dim3(Cfg::NT), Cfg::LDS_BYTES, st, q, k, v, o,
+                       dO, lse, dq, dk, dv, rowsc, H, N, rs.qkv, rs.o, (int)nblocks, scale * kLog2e, scale);
+    const hipError_t e = hipGetLastError();
+    return e == hipSuccess ? AVION_OK : hip_fail(e, "launch avion_bwd_small_kernel");
+}
+
 // Kernel instances: four wavefronts per workgroup for every kernel, head size, format and masking.
 // Calls f(head dim, element format, causal) with the three as compile-time tags.
 template <typename T>
@@ -205,6 +222,23 @@ int dkdv_impl(const void* q, const void* k, const void* v, const float* lse, con
     });
 }
 
+// Whole backward in one launch (N <= 128); arguments already checked by the caller.
+int bwd_small_impl(const void* q, const void* k, const void* v, const void* o, const float* lse, const void* dO, void* dq,
+                   void* dk, void* dv, int B, int H, int N, int d, int packed, Variant var, float scale, void* workspace,
+                   void* stream)
+{
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const Strides rs{packed * H * d, H * d};
+    float* rowsc = static_cast<float*>(workspace);
+    const raw16 *qq = static_cast<const raw16*>(q), *kk = static_cast<const raw16*>(k), *vv = static_cast<const raw16*>(v),
+                *oo = static_cast<const raw16*>(o), *gg = static_cast<const raw16*>(dO);
+    raw16 *dqq = static_cast<raw16*>(dq), *dkk = static_cast<raw16*>(dk), *dvv = static_cast<raw16*>(dv);
+    return by_variant(var, d, [&](auto dim, auto fmt, auto causal) {
+        return launch_bwd_small<decltype(dim)::value, 4, typename decltype(fmt)::type, decltype(causal)::value>(
+            qq, kk, vv, oo, gg, lse, dqq, dkk, dvv, rowsc, B, H, N, rs, scale, st);
+    });
+}
+
 int bwd_impl(const void* q, const void* k, const void* v, const void* o, const float* lse, const void* dO, void* dq,
              void* dk, void* dv, int B, int H, int N, int d, Variant var, float scale, void* workspace, size_t workspace_bytes,
              void* stream)
@@ -217,6 +251,7 @@ int bwd_impl(const void* q, const void* k, const void* v, const void* o, const f
     for (const void* p : ptrs)
         if (!aligned16(p)) return AVION_EUNSUPPORTED;
     if (!workspace_ok(workspace, workspace_bytes, B, H, N, d)) return AVION_EWORKSPACE;
+    if (N <= BwdSmallCfg<64, 4>::MAX_N) return bwd_small_impl(q, k, v, o, lse, dO, dq, dk, dv, B, H, N, d, 1, var, scale, workspace, stream);
     const int rq = dq_impl(q, k, v, o, lse, dO, dq, B, H, N, d, 1, var, scale, workspace, workspace_bytes, stream);
     if (rq != AVION_OK) return rq;
     return dkdv_impl(q, k, v, lse, dO, dk, dv, B, H, N, d, 1, var, scale, workspace, workspace_bytes, stream);
@@ -340,6 +375,9 @@ int avion_attn_bwd_qkvpacked(const void* qkv, const void* o, const float* lse, c
     if (!workspace_ok(workspace, workspace_bytes, B, H, N, d)) return AVION_EWORKSPACE;
     const Planes in(qkv, H, d), out(dqkv, H, d);
     void *dq = const_cast<char*>(out.q), *dk = const_cast<char*>(out.k), *dv = const_cast<char*>(out.v);
+    if (N <= BwdSmallCfg<64, 4>::MAX_N)
+        return bwd_small_impl(in.q, in.k, in.v, o, lse, dO, dq, dk, dv, B, H, N, d, 3, Variant{false, false}, scale, workspace,
+                              stream);
     const int rq = dq_impl(in.q, in.k, in.v, o, lse, dO, dq, B, H, N, d, 3, Variant{false, false}, scale, workspace,
                            workspace_bytes, stream);
     if (rq != AVION_OK) return rq;

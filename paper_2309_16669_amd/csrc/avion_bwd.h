@@ -44,22 +44,18 @@ struct DqCfg {
     static constexpr int WAVES_PER_SIMD = D == 64 ? 3 : 2;  // LDS would allow more; registers do not
 };
 
+// The work of one workgroup: query block qb of (batch, head) bh.
 template <int D, int NW, typename E, bool CAUSAL>
-__global__ void __launch_bounds__(NW * 64, (DqCfg<D, NW>::WAVES_PER_SIMD))
-avion_dq_kernel(const raw16* __restrict__ q, const raw16* __restrict__ k, const raw16* __restrict__ v,
-                    const raw16* __restrict__ o, const raw16* __restrict__ dO, const float* __restrict__ lse,
-                    raw16* __restrict__ dq, float* __restrict__ rowsc, int H, int N, int rs_qkv, int rs_o, int nqb,
-                    int nblocks, float cs, float scale)
+DEVINL void avion_dq_body(char* smem, const raw16* __restrict__ q, const raw16* __restrict__ k,
+                          const raw16* __restrict__ v, const raw16* __restrict__ o, const raw16* __restrict__ dO,
+                          const float* __restrict__ lse, raw16* __restrict__ dq, float* __restrict__ rowsc, int H, int N,
+                          int rs_qkv, int rs_o, int bh, int qb, float cs, float scale)
 {
     using Cfg = DqCfg<D, NW>;
     using Ring = typename Cfg::Ring;
     constexpr int BN = Cfg::BN, BM = Cfg::BM, STRIDE = Ring::STRIDE;
     constexpr int KS = D / 16, CT = (D + 31) / 32;
-    extern __shared__ __attribute__((aligned(16))) char smem[];
 
-    const int logical = xcd_local_id(blockIdx.x, nblocks);
-    if (logical < 0) return;
-    const int bh = logical / nqb, qb = logical % nqb;
     const int b = bh / H, h = bh % H;
     const int tid = threadIdx.x, lane = tid % 64, l32 = lane % 32, g = lane / 32;
     const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
@@ -162,6 +158,20 @@ avion_dq_kernel(const raw16* __restrict__ q, const raw16* __restrict__ k, const 
     RowStore<D, E>::run(smem + wave * RowStore<D, E>::BYTES, acc, scale, dq + head_off + (long)q0 * rs, rs, N - q0, lane);
 }
 
+template <int D, int NW, typename E, bool CAUSAL>
+__global__ void __launch_bounds__(NW * 64, (DqCfg<D, NW>::WAVES_PER_SIMD))
+avion_dq_kernel(const raw16* __restrict__ q, const raw16* __restrict__ k, const raw16* __restrict__ v,
+                    const raw16* __restrict__ o, const raw16* __restrict__ dO, const float* __restrict__ lse,
+                    raw16* __restrict__ dq, float* __restrict__ rowsc, int H, int N, int rs_qkv, int rs_o, int nqb,
+                    int nblocks, float cs, float scale)
+{
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const int logical = xcd_local_id(blockIdx.x, nblocks);
+    if (logical < 0) return;
+    avion_dq_body<D, NW, E, CAUSAL>(smem, q, k, v, o, dO, lse, dq, rowsc, H, N, rs_qkv, rs_o, logical / nqb, logical % nqb,
+                                    cs, scale);
+}
+
 // ------------------------------------------------------------------------------------------ dK, dV
 // One wavefront owns 32 keys (K, V as B-operand fragments); the workgroup's NW wavefronts share
 // (Q | dO | per-query scalars) tiles of 64 queries.  The dP accumulator starts from -delta, so the
@@ -176,23 +186,19 @@ struct DkvCfg {
     static constexpr int WAVES_PER_SIMD = 2;  // a floor for the register budget; D = 64 fits three
 };
 
+// The work of one workgroup: key block kb of (batch, head) bh.
 template <int D, int NW, typename E, bool CAUSAL>
-__global__ void __launch_bounds__(NW * 64, (DkvCfg<D, NW>::WAVES_PER_SIMD))
-avion_dkdv_kernel(const raw16* __restrict__ q, const raw16* __restrict__ k, const raw16* __restrict__ v,
-                      const raw16* __restrict__ dO, const float* __restrict__ rowsc, raw16* __restrict__ dk,
-                      raw16* __restrict__ dv, int H, int N, int rs_qkv, int rs_o, int nkb, int nblocks, float cs,
-                      float scale)
+DEVINL void avion_dkdv_body(char* smem, const raw16* __restrict__ q, const raw16* __restrict__ k,
+                            const raw16* __restrict__ v, const raw16* __restrict__ dO, const float* __restrict__ rowsc,
+                            raw16* __restrict__ dk, raw16* __restrict__ dv, int H, int N, int rs_qkv, int rs_o, int bh,
+                            int kb, float cs, float scale)
 {
     using Cfg = DkvCfg<D, NW>;
     using Ring = typename Cfg::Ring;
     constexpr int BQ = Cfg::BQ, BNK = Cfg::BNK, STRIDE = Ring::STRIDE;
     constexpr int KS = D / 16, CT = (D + 31) / 32;
     constexpr int OFF_G = Ring::OFF_B, OFF_ROW = Ring::OFF_SCALARS;
-    extern __shared__ __attribute__((aligned(16))) char smem[];
 
-    const int logical = xcd_local_id(blockIdx.x, nblocks);
-    if (logical < 0) return;
-    const int bh = logical / nkb, kb = logical % nkb;
     const int b = bh / H, h = bh % H;
     const int tid = threadIdx.x, lane = tid % 64, l32 = lane % 32, g = lane / 32;
     const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
@@ -300,4 +306,53 @@ avion_dkdv_kernel(const raw16* __restrict__ q, const raw16* __restrict__ k, cons
     char* region = smem + wave * RowStore<D, E>::BYTES;
     RowStore<D, E>::run(region, dka, scale, dk + head_off + (long)k0 * rs, rs, N - k0, lane);
     RowStore<D, E>::run(region, dva, 1.0f, dv + head_off + (long)k0 * rs, rs, N - k0, lane);
+}
+
+template <int D, int NW, typename E, bool CAUSAL>
+__global__ void __launch_bounds__(NW * 64, (DkvCfg<D, NW>::WAVES_PER_SIMD))
+avion_dkdv_kernel(const raw16* __restrict__ q, const raw16* __restrict__ k, const raw16* __restrict__ v,
+                      const raw16* __restrict__ dO, const float* __restrict__ rowsc, raw16* __restrict__ dk,
+                      raw16* __restrict__ dv, int H, int N, int rs_qkv, int rs_o, int nkb, int nblocks, float cs,
+                      float scale)
+{
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const int logical = xcd_local_id(blockIdx.x, nblocks);
+    if (logical < 0) return;
+    avion_dkdv_body<D, NW, E, CAUSAL>(smem, q, k, v, dO, rowsc, dk, dv, H, N, rs_qkv, rs_o, logical / nkb, logical % nkb, cs,
+                                      scale);
+}
+
+// ------------------------------------------------------------------------- whole backward, short sequences
+// For N <= 32*NW one workgroup covers all queries and all keys of a (batch, head): the two passes
+// then run back to back inside one workgroup, so that the second pass finds Q, K, V and dO in the
+// L2 where the first one has just pulled them (launched separately it would fetch them from HBM
+// again), and one launch is saved.  Same arithmetic, same bits as the two kernels.  The per-query
+// scalars still travel through the workspace: a workgroup-scope fence makes the first pass's stores visible
+// before the second pass's tile mover reads them, the barrier also frees the LDS the first pass
+// used for its epilogue.
+template <int D, int NW>
+struct BwdSmallCfg {
+    static constexpr int NT = NW * 64;
+    static constexpr int MAX_N = 32 * NW;
+    static constexpr int LDS_BYTES =
+        DqCfg<D, NW>::LDS_BYTES > DkvCfg<D, NW>::LDS_BYTES ? DqCfg<D, NW>::LDS_BYTES : DkvCfg<D, NW>::LDS_BYTES;
+};
+
+template <int D, int NW, typename E, bool CAUSAL>
+__global__ void __launch_bounds__(NW * 64, (DkvCfg<D, NW>::WAVES_PER_SIMD))
+avion_bwd_small_kernel(const raw16* __restrict__ q, const raw16* __restrict__ k, const raw16* __restrict__ v,
+                       const raw16* __restrict__ o, const raw16* __restrict__ dO, const float* __restrict__ lse,
+                       raw16* __restrict__ dq, raw16* __restrict__ dk, raw16* __restrict__ dv, float* __restrict__ rowsc,
+                       int H, int N, int rs_qkv, int rs_o, int nblocks, float cs, float scale)
+{
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const int bh = xcd_local_id(blockIdx.x, nblocks);
+    if (bh < 0) return;
+    avion_dq_body<D, NW, E, CAUSAL>(smem, q, k, v, o, dO, lse, dq, rowsc, H, N, rs_qkv, rs_o, bh, 0, cs, scale);
+    // Workgroup scope is enough (writer and reader wavefronts sit on one compute unit and share its
+    // vector cache) and is only a wait for the stores; a device-scope fence would write back and
+    // invalidate the L2 once per workgroup.
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+    __syncthreads();
+    avion_dkdv_body<D, NW, E, CAUSAL>(smem, q, k, v, dO, rowsc, dk, dv, H, N, rs_qkv, rs_o, bh, 0, cs, scale);
 }
