@@ -117,6 +117,23 @@ def test_packed_entry_points_reject_bad_arguments_without_launching(kwargs, code
         assert rc == code
 
 
+@pytest.mark.parametrize("suffix", ["", "_f16", "_causal"])
+def test_every_variant_checks_its_arguments(suffix):
+    # the fp16 and causal entry points share the checks of the bf16 ones
+    lib = av.load_library()
+    fwd, bwd = getattr(lib, "avion_attn_fwd" + suffix), getattr(lib, "avion_attn_bwd" + suffix)
+    c = ctypes.c_float
+    assert fwd(FAKE, FAKE, FAKE, FAKE, FAKE, 1, 2, 64, 48, c(0.1), None) == av.EUNSUPPORTED
+    assert fwd(FAKE, 0, FAKE, FAKE, FAKE, 1, 2, 64, 64, c(0.1), None) == av.EINVAL
+    assert fwd(FAKE, FAKE, FAKE, FAKE, FAKE, 1, 2, 0, 64, c(0.1), None) == av.EINVAL
+    assert fwd(FAKE, FAKE, FAKE, FAKE + 4, FAKE, 1, 2, 64, 64, c(0.1), None) == av.EUNSUPPORTED
+    assert bwd(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 1, 2, 64, 80, c(-1.0), FAKE, 1 << 20, None) == av.EINVAL
+    assert bwd(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 1, 2, 64, 80, c(0.1), FAKE, 8, None) == av.EWORKSPACE
+    assert bwd(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 0, 1, 2, 64, 80, c(0.1), FAKE, 1 << 20, None) == av.EINVAL
+    # short sequences take the one-launch path: same checks before anything is launched
+    assert bwd(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 1, 2, 16, 64, c(0.1), FAKE + 64, 1 << 20, None) == av.EWORKSPACE
+
+
 def test_binding_does_not_import_the_oracle():
     import sys
     src = open(os.path.join(ROOT, "paper_2309_16669_amd", "__init__.py")).read()
