@@ -41,7 +41,7 @@ extern "C" {
 #endif
 
 #define AVION_OK 0
-#define AVION_EINVAL (-1)       /* null pointer; B, H or N < 1; scale not finite or <= 0            */
+#define AVION_EINVAL (-1)       /* null pointer; B, H or N < 1; scale not finite or < 2^-60         */
 #define AVION_EUNSUPPORTED (-2) /* d not in {64, 80}; misaligned pointer; N > 2^24; B*H > 2^24     */
 #define AVION_EWORKSPACE (-3)   /* workspace NULL, misaligned (256 B) or smaller than required      */
 #define AVION_EHIP (-4)         /* a HIP launch failed; avion_last_hip_error() has the runtime text */
@@ -60,7 +60,9 @@ const char *avion_last_hip_error(void);
  *   q, k, v : in,  bf16 [B,N,H,d]
  *   o       : out, bf16 [B,N,H,d], fully overwritten
  *   lse     : out, fp32 [B,H,N],   fully overwritten; needed by avion_attn_bwd
- *   scale   : multiplies the dot products (1/sqrt(d) in a ViT); must be finite and > 0
+ *   scale   : multiplies the dot products (1/sqrt(d) in a ViT); must be finite and >= 2^-60
+ *             (keys outside a ragged tile or a causal mask are removed by a score of -1e30 times
+ *             scale, which must stay far below every real score)
  * Extra device memory used: none.
  */
 int avion_attn_fwd(const void *q, const void *k, const void *v, void *o, float *lse,

@@ -8,6 +8,7 @@
 #include <cstdint>
 #include <cstdio>
 #include <cstdlib>
+#include <atomic>
 #include <cstring>
 
 #include "avion_bwd.h"
@@ -37,10 +38,15 @@ struct Variant {
     bool causal;
 };
 
+constexpr float kMinScale = 8.673617379884035e-19f;  // 2^-60
+
 int check_shape(int B, int H, int N, int d, float scale, int packed = 1)
 {
     if (B < 1 || H < 1 || N < 1) return AVION_EINVAL;
-    if (!(scale > 0.f) || !std::isfinite(scale)) return AVION_EINVAL;
+    // Keys past the end of a ragged tile (and keys a causal query must not see) are removed by a
+    // score of -1e30 that is then multiplied by scale*log2(e); the product has to stay far below any
+    // real score for the weight to come out as exactly 0, hence the floor of 2^-60 on scale.
+    if (!(scale >= kMinScale) || !std::isfinite(scale)) return AVION_EINVAL;
     if (d != 64 && d != 80) return AVION_EUNSUPPORTED;
     if (N > (1 << 24) || (long long)B * H > (1 << 24)) return AVION_EUNSUPPORTED;
     // one (batch, head) slice is addressed with 32-bit byte offsets (buffer loads), and tile loads
@@ -58,10 +64,25 @@ bool grid_for(long long nblocks, unsigned* grid)
     return true;
 }
 
+// Raises the kernel's dynamic LDS limit once; `done` is the caller's per-instance flag.  A failure
+// is not remembered, so the next call tries again.
 template <typename K>
-hipError_t allow_lds(K kernel, int bytes)
+hipError_t allow_lds(K kernel, int bytes, std::atomic<bool>& done)
 {
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (done.load(std::memory_order_acquire)) return hipSuccess;
+    const hipError_t e =
+        hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess) done.store(true, std::memory_order_release);
+    return e;
+}
+
+// Result of the launch just made on this thread.  Errors left behind by earlier, unrelated work of
+// the caller are cleared before the launch (begin_launch) so that they are not mistaken for it.
+void begin_launch() { (void)hipGetLastError(); }
+int end_launch(const char* what)
+{
+    const hipError_t e = hipGetLastError();
+    return e == hipSuccess ? AVION_OK : hip_fail(e, what);
 }
 
 template <int D, int NW, typename E, bool CAUSAL>
@@ -69,16 +90,17 @@ int launch_fwd(const raw16* q, const raw16* k, const raw16* v, raw16* o, float* 
                float scale, hipStream_t st)
 {
     using Cfg = FwdCfg<D, NW>;
-    static hipError_t attr = allow_lds(avion_fwd_kernel<D, NW, E, CAUSAL>, Cfg::LDS_BYTES);
+    static std::atomic<bool> lds_allowed{false};
+    const hipError_t attr = allow_lds(avion_fwd_kernel<D, NW, E, CAUSAL>, Cfg::LDS_BYTES, lds_allowed);
     if (attr != hipSuccess) return hip_fail(attr, "hipFuncSetAttribute(fwd)");
     const int nqb = (N + Cfg::BM - 1) / Cfg::BM;
     const long long nblocks = (long long)nqb * B * H;
     unsigned grid;
     if (!grid_for(nblocks, &grid)) return AVION_EUNSUPPORTED;
+    begin_launch();
     hipLaunchKernelGGL((avion_fwd_kernel<D, NW, E, CAUSAL>), dim3(grid), dim3(Cfg::NT), Cfg::LDS_BYTES, st, q, k, v, o, lse, H, N, rs.qkv,
                        rs.o, nqb, (int)nblocks, scale * kLog2e);
-    const hipError_t e = hipGetLastError();
-    return e == hipSuccess ? AVION_OK : hip_fail(e, "launch avion_fwd_kernel");
+    return end_launch("launch avion_fwd_kernel");
 }
 
 template <int D, int NW, typename E, bool CAUSAL>
@@ -86,16 +108,17 @@ int launch_dq(const raw16* q, const raw16* k, const raw16* v, const raw16* o, co
               float* rowsc, int B, int H, int N, Strides rs, float scale, hipStream_t st)
 {
     using Cfg = DqCfg<D, NW>;
-    static hipError_t attr = allow_lds(avion_dq_kernel<D, NW, E, CAUSAL>, Cfg::LDS_BYTES);
+    static std::atomic<bool> lds_allowed{false};
+    const hipError_t attr = allow_lds(avion_dq_kernel<D, NW, E, CAUSAL>, Cfg::LDS_BYTES, lds_allowed);
     if (attr != hipSuccess) return hip_fail(attr, "hipFuncSetAttribute(dq)");
     const int nqb = (N + Cfg::BM - 1) / Cfg::BM;
     const long long nblocks = (long long)nqb * B * H;
     unsigned grid;
     if (!grid_for(nblocks, &grid)) return AVION_EUNSUPPORTED;
+    begin_launch();
     hipLaunchKernelGGL((avion_dq_kernel<D, NW, E, CAUSAL>), dim3(grid), dim3(Cfg::NT), Cfg::LDS_BYTES, st, q, k, v, o, dO, lse, dq,
                        rowsc, H, N, rs.qkv, rs.o, nqb, (int)nblocks, scale * kLog2e, scale);
-    const hipError_t e = hipGetLastError();
-    return e == hipSuccess ? AVION_OK : hip_fail(e, "launch avion_dq_kernel");
+    return end_launch("launch avion_dq_kernel");
 }
 
 template <int D, int NW, typename E, bool CAUSAL>
@@ -103,16 +126,17 @@ int launch_dkdv(const raw16* q, const raw16* k, const raw16* v, const raw16* dO,
                 int B, int H, int N, Strides rs, float scale, hipStream_t st)
 {
     using Cfg = DkvCfg<D, NW>;
-    static hipError_t attr = allow_lds(avion_dkdv_kernel<D, NW, E, CAUSAL>, Cfg::LDS_BYTES);
+    static std::atomic<bool> lds_allowed{false};
+    const hipError_t attr = allow_lds(avion_dkdv_kernel<D, NW, E, CAUSAL>, Cfg::LDS_BYTES, lds_allowed);
     if (attr != hipSuccess) return hip_fail(attr, "hipFuncSetAttribute(dkdv)");
     const int nkb = (N + Cfg::BNK - 1) / Cfg::BNK;
     const long long nblocks = (long long)nkb * B * H;
     unsigned grid;
     if (!grid_for(nblocks, &grid)) return AVION_EUNSUPPORTED;
+    begin_launch();
     hipLaunchKernelGGL((avion_dkdv_kernel<D, NW, E, CAUSAL>), dim3(grid), dim3(Cfg::NT), Cfg::LDS_BYTES, st, q, k, v, dO, rowsc, dk,
                        dv, H, N, rs.qkv, rs.o, nkb, (int)nblocks, scale * kLog2e, scale);
-    const hipError_t e = hipGetLastError();
-    return e == hipSuccess ? AVION_OK : hip_fail(e, "launch avion_dkdv_kernel");
+    return end_launch("launch avion_dkdv_kernel");
 }
 
 template <int D, int NW, typename E, bool CAUSAL>
@@ -121,15 +145,16 @@ int launch_bwd_small(const raw16* q, const raw16* k, const raw16* v, const raw16
                      hipStream_t st)
 {
     using Cfg = BwdSmallCfg<D, NW>;
-    static hipError_t attr = allow_lds(avion_bwd_small_kernel<D, NW, E, CAUSAL>, Cfg::LDS_BYTES);
+    static std::atomic<bool> lds_allowed{false};
+    const hipError_t attr = allow_lds(avion_bwd_small_kernel<D, NW, E, CAUSAL>, Cfg::LDS_BYTES, lds_allowed);
     if (attr != hipSuccess) return hip_fail(attr, "hipFuncSetAttribute(bwd_small)");
     const long long nblocks = (long long)B * H;
     unsigned grid;
     if (!grid_for(nblocks, &grid)) return AVION_EUNSUPPORTED;
+    begin_launch();
     hipLaunchKernelGGL((avion_bwd_small_kernel<D, NW, E, CAUSAL>), dim3(grid), dim3(Cfg::NT), Cfg::LDS_BYTES, st, q, k, v, o,
                        dO, lse, dq, dk, dv, rowsc, H, N, rs.qkv, rs.o, (int)nblocks, scale * kLog2e, scale);
-    const hipError_t e = hipGetLastError();
-    return e == hipSuccess ? AVION_OK : hip_fail(e, "launch avion_bwd_small_kernel");
+    return end_launch("launch avion_bwd_small_kernel");
 }
 
 // Kernel instances: four wavefronts per workgroup for every kernel, head size, format and masking.
@@ -274,13 +299,13 @@ struct Planes {
 
 extern "C" {
 
-int avion_version(void) { return 200; }
+int avion_version(void) { return 20100; }  // 2.1.0
 
 const char* avion_strerror(int code)
 {
     switch (code) {
         case AVION_OK: return "ok";
-        case AVION_EINVAL: return "invalid argument (null pointer, B/H/N < 1, or scale not finite and positive)";
+        case AVION_EINVAL: return "invalid argument (null pointer, B/H/N < 1, or scale not finite or below 2^-60)";
         case AVION_EUNSUPPORTED: return "unsupported shape or alignment (d must be 64 or 80; pointers 16-byte aligned)";
         case AVION_EWORKSPACE: return "workspace missing, misaligned or too small";
         case AVION_EHIP: return "HIP runtime error (see avion_last_hip_error)";

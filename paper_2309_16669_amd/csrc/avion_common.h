@@ -235,9 +235,14 @@ DEVINL RawBuffer pick(bool first, const RawBuffer& a, const RawBuffer& b)
     for (int i = 0; i < 4; ++i) r.words[i] = __builtin_amdgcn_readfirstlane(r.words[i]);
     return r;
 }
+// Wait states: the compiler's hazard recogniser does not look inside the statement.  M0 must be
+// written at least one wait state before the load that reads it, and a scalar register that a
+// vector instruction (v_readfirstlane) has just produced -- the descriptor words or lds_addr may be
+// such registers -- needs five wait states before a vector-memory instruction reads it.  s_mov plus
+// s_nop 4 (five wait states) puts six between anything before the statement and the load.
 DEVINL void load_to_lds16(const RawBuffer& buf, unsigned lds_addr, unsigned voff)
 {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 4\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
                  :
                  : "s"(lds_addr), "v"(voff), "s"(buf.words)
                  : "memory", "m0");
