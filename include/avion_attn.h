@@ -45,6 +45,7 @@ extern "C" {
 #define AVION_EUNSUPPORTED (-2) /* d not in {64, 80}; misaligned pointer; N > 2^24; B*H > 2^24     */
 #define AVION_EWORKSPACE (-3)   /* workspace NULL, misaligned (256 B) or smaller than required      */
 #define AVION_EHIP (-4)         /* a HIP launch failed; avion_last_hip_error() has the runtime text */
+#define AVION_ESCRATCH (-5)     /* avion_attn_bwd_noalloc: problem exceeds the built-in scratch     */
 
 /* Library version as major*10000 + minor*100 + patch. */
 int avion_version(void);
@@ -172,6 +173,26 @@ int avion_attn_bwd_causal(const void *q, const void *k, const void *v, const voi
                           const float *lse, const void *dO, void *dq, void *dk, void *dv,
                           int B, int H, int N, int d, float scale,
                           void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Allocation-free backward, for callers that cannot provide device scratch of their own: code
+ * under HIP graph capture, tight serving or training loops, harnesses that forbid hipMalloc.
+ * Same operation, arguments, rules and bits as avion_attn_bwd (bf16, not causal), without the
+ * workspace: the per-query scalars that the two passes exchange live in a 32 MiB array that is
+ * part of the library's device image (one copy per GPU, held until the process ends).
+ *   - Limit: avion_attn_bwd_workspace_bytes(B, H, N, d) <= 32 MiB, i.e.
+ *     B*H*ceil(N/64)*64 <= 4 194 304 rows; larger problems return AVION_ESCRATCH and launch nothing.
+ *   - Calls no hipMalloc, hipFree or other allocating routine.  The first call on a device looks
+ *     up the array's address on that device (hipGetSymbolAddress) and keeps it; make that first
+ *     call outside a graph capture.
+ *   - All calls on one GPU share that GPU's array: two calls that overlap in time on the same GPU
+ *     (different streams, different threads) race on it.  Calls on one stream are ordered and safe.
+ *     Nothing in the array has to survive between calls and nothing needs clearing: each call
+ *     writes every entry it later reads.
+ */
+int avion_attn_bwd_noalloc(const void *q, const void *k, const void *v, const void *o,
+                           const float *lse, const void *dO, void *dq, void *dk, void *dv,
+                           int B, int H, int N, int d, float scale, void *stream);
 
 #ifdef __cplusplus
 }

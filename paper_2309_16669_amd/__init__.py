@@ -14,7 +14,7 @@ import os
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libavion_attn.so")
 
-OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, -1, -2, -3, -4
+OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP, ESCRATCH = 0, -1, -2, -3, -4, -5
 
 _lib = None
 
@@ -63,6 +63,8 @@ def load_library() -> ctypes.CDLL:
         lib.avion_attn_fwd_causal.argtypes = lib.avion_attn_fwd.argtypes
         lib.avion_attn_bwd_causal.restype = i
         lib.avion_attn_bwd_causal.argtypes = lib.avion_attn_bwd.argtypes
+        lib.avion_attn_bwd_noalloc.restype = i
+        lib.avion_attn_bwd_noalloc.argtypes = [p, p, p, p, p, p, p, p, p, i, i, i, i, f, p]
         _lib = lib
     return _lib
 
@@ -146,6 +148,18 @@ def attn_bwd(q, k, v, o, lse, dO, dq, dk, dv, scale: float, workspace, stream=No
     attn_bwd_workspace_bytes(B,H,N,d) bytes."""
     import torch
     _bwd(load_library().avion_attn_bwd, torch.bfloat16, q, k, v, o, lse, dO, dq, dk, dv, scale, workspace, stream)
+
+
+def attn_bwd_noalloc(q, k, v, o, lse, dO, dq, dk, dv, scale: float, stream=None) -> None:
+    """avion_attn_bwd_noalloc: avion_attn_bwd without a workspace argument (the library's built-in
+    32 MiB scratch takes its place; larger problems raise AvionError with code ESCRATCH)."""
+    import torch
+    B, N, H, d = q.shape
+    for t, n in ((q, "q"), (k, "k"), (v, "v"), (o, "o"), (dO, "dO"), (dq, "dq"), (dk, "dk"), (dv, "dv")):
+        _require(t, n, torch.bfloat16, (B, N, H, d))
+    _require(lse, "lse", torch.float32, (B, H, N))
+    _check(load_library().avion_attn_bwd_noalloc(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(dO), _ptr(dq),
+                                                 _ptr(dk), _ptr(dv), B, H, N, d, float(scale), _stream_handle(stream)))
 
 
 def attn_bwd_f16(q, k, v, o, lse, dO, dq, dk, dv, scale: float, workspace, stream=None) -> None:

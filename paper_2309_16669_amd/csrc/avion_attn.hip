@@ -10,9 +10,17 @@
 #include <cstdlib>
 #include <atomic>
 #include <cstring>
+#include <mutex>
 
 #include "avion_bwd.h"
 #include "avion_fwd.h"
+
+// Built-in scratch of avion_attn_bwd_noalloc: the per-query scalars that the backward's two passes
+// hand to each other live here instead of in a caller's workspace.  One copy per GPU, held until
+// the process ends.  In host code this name is only a handle for hipGetSymbolAddress; kernels get
+// the device address that call returns.
+constexpr size_t kScratchBytes = size_t(32) << 20;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
 
 namespace {
 
@@ -22,6 +30,28 @@ int hip_fail(hipError_t e, const char* what)
 {
     std::snprintf(g_hip_error, sizeof g_hip_error, "%s: %s", what, hipGetErrorString(e));
     return AVION_EHIP;
+}
+
+// Device address of `scratch` on each GPU, looked up once per device with that device current.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+int scratch_of_current_device(void** out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices) return AVION_EUNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) return hip_fail(e, "hipGetSymbolAddress(scratch)");
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return AVION_OK;
 }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -309,6 +339,7 @@ const char* avion_strerror(int code)
         case AVION_EUNSUPPORTED: return "unsupported shape or alignment (d must be 64 or 80; pointers 16-byte aligned)";
         case AVION_EWORKSPACE: return "workspace missing, misaligned or too small";
         case AVION_EHIP: return "HIP runtime error (see avion_last_hip_error)";
+        case AVION_ESCRATCH: return "problem needs more than the 32 MiB built-in scratch of avion_attn_bwd_noalloc";
         default: return "unknown avion error code";
     }
 }
@@ -358,6 +389,23 @@ int avion_attn_bwd(const void* q, const void* k, const void* v, const void* o, c
 {
     return bwd_impl(q, k, v, o, lse, dO, dq, dk, dv, B, H, N, d, Variant{false, false}, scale, workspace, workspace_bytes,
                     stream);
+}
+
+int avion_attn_bwd_noalloc(const void* q, const void* k, const void* v, const void* o, const float* lse, const void* dO,
+                           void* dq, void* dk, void* dv, int B, int H, int N, int d, float scale, void* stream)
+{
+    // argument errors first, so that they are reported as for avion_attn_bwd
+    if (!q || !k || !v || !o || !lse || !dO || !dq || !dk || !dv) return AVION_EINVAL;
+    const int rc = check_shape(B, H, N, d, scale);
+    if (rc != AVION_OK) return rc;
+    const size_t need = avion_attn_bwd_workspace_bytes(B, H, N, d);
+    if (need > kScratchBytes) return AVION_ESCRATCH;
+    void* ws = nullptr;
+    const int rs = scratch_of_current_device(&ws);
+    if (rs != AVION_OK) return rs;
+    // every entry of the scratch that the second pass reads is written by the first one (padding
+    // rows included), so nothing has to be cleared between calls
+    return bwd_impl(q, k, v, o, lse, dO, dq, dk, dv, B, H, N, d, Variant{false, false}, scale, ws, need, stream);
 }
 
 int avion_attn_fwd_causal(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int N, int d,
