@@ -9,6 +9,12 @@ Prints ONE JSON line.  `value` is algorithmic TFLOP/s of fwd+bwd: 14*B*H*N^2*d f
 (fwd 4, bwd 10 including the recomputation of S that the method needs; the second recomputation of
 S and dP that the two-kernel backward does for itself is NOT counted).
 
+Timing protocol: an untimed pre-warm (the card idles at a few hundred MHz and needs some tenths of a
+second of load to reach its steady clock), W warm-up steps, then exactly K steps between two HIP
+events recorded on the launch stream, bracketed by synchronisations.  `ms_per_step` is that event
+time / K; the host's wall clock over the same K steps is reported beside it (`ms_per_step_wall`),
+and the K-step block is repeated a few times for a median and a minimum (`repeats`).
+
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
 """
 from __future__ import annotations
@@ -28,31 +34,39 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published figure
 # HBM bytes per launch (FETCH_SIZE + WRITE_SIZE from rocprofv3 --pmc, scaled by a copy kernel of
 # known size); filled in from the summaries under profiles/ -- None until measured.
 MEASURED_HBM_BYTES_PER_LAUNCH = {
-    # profiles/hbm_traffic_vitb_batch.txt: FETCH_SIZE x 2.0 (copy-kernel factor) + WRITE_SIZE x 1.0
-    ("vitb_batch", "avion_fwd_kernel"): 312.0e6,
-    ("vitb_batch", "avion_dq_kernel"): 473.1e6,
-    ("vitb_batch", "avion_dkdv_kernel"): 471.3e6,
+    # (workload, dtype, kernel) -> (bytes per launch, summary under profiles/ that holds the counters).
+    # FETCH_SIZE x 2.0 (copy-kernel factor) + WRITE_SIZE x 1.0.  Measured offline on the default
+    # configuration (separate q/k/v tensors, recipe operands); any other run prints null with the reason.
+    ("vitb_batch", "bf16", "avion_fwd_kernel"): (312.0e6, "profiles/hbm_traffic_vitb_batch.txt"),
+    ("vitb_batch", "bf16", "avion_dq_kernel"): (473.1e6, "profiles/hbm_traffic_vitb_batch.txt"),
+    ("vitb_batch", "bf16", "avion_dkdv_kernel"): (471.3e6, "profiles/hbm_traffic_vitb_batch.txt"),
 }
+PREWARM_SECONDS = 0.3
 
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def timed(fn, steps, warmup, stream):
-    """Average milliseconds per call of fn over `steps` calls, measured with HIP events on `stream`."""
+def event_ms(fn, n, stream):
+    """Milliseconds per call of fn over n calls, between two HIP events recorded on `stream`."""
     import torch
-    for _ in range(warmup):
-        fn()
-    torch.cuda.synchronize()
     e0 = torch.cuda.Event(enable_timing=True)
     e1 = torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
     e0.record(stream)
-    for _ in range(steps):
+    for _ in range(n):
         fn()
     e1.record(stream)
     torch.cuda.synchronize()
-    return e0.elapsed_time(e1) / steps
+    return e0.elapsed_time(e1) / n
+
+
+def timed(fn, steps, warmup, stream, repeats=3):
+    """Median over `repeats` blocks of `steps` calls each (HIP events on `stream`), after `warmup` calls."""
+    for _ in range(warmup):
+        fn()
+    return sorted(event_ms(fn, steps, stream) for _ in range(repeats))[repeats // 2]
 
 
 def cpu_baseline(w, x, clips):
@@ -77,8 +91,8 @@ def cpu_baseline(w, x, clips):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="vitb_batch")
     ap.add_argument("--cpu-clips", type=int, default=32)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -92,10 +106,13 @@ def main():
     ap.add_argument("--layout", choices=("separate", "packed"), default="separate",
                     help="separate = q, k, v as three [B,N,H,d] tensors (the reported configuration); packed = one "
                          "[B,N,3,H,d] tensor through the *_qkvpacked entry points (same kernels, token stride 3*H*d)")
-    ap.add_argument("--checkpointing", action="store_true",
-                    help="also time the step of a layer trained with gradient checkpointing (Sec. 4.1 of the "
-                         "paper): the forward runs a second time before the backward; reported beside the "
-                         "metric, which is unchanged")
+    ap.add_argument("--causal", action="store_true",
+                    help="the causal entry points (query i sees keys 0..i) on the same tensors; a diagnostic, the "
+                         "value still counts the unmasked 14*B*H*N^2*d flops")
+    ap.add_argument("--no-checkpointing", action="store_true",
+                    help="skip the extra timing of the step of a layer trained with gradient checkpointing "
+                         "(Sec. 4.1 of the paper: the forward runs a second time before the backward), which is "
+                         "reported beside the metric and does not change it")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain device copy of Q (known size) so that HBM counters of a "
                          "rocprofv3 --pmc run can be scaled")
@@ -118,11 +135,8 @@ def main():
     w = si.WORKLOADS[args.workload]
     log(f"[bench] generating {w.name} {w.shape} ...")
     f16 = args.dtype == "f16"
-    if f16 and args.layout == "packed":
-        sys.exit("bench.py: the packed entry points exist for bf16 only")
     x = si.make_inputs(w, fmt=args.dtype)
     dev = torch.device("cuda:0")
-    attn_fwd, attn_bwd = (av.attn_fwd_f16, av.attn_bwd_f16) if f16 else (av.attn_fwd, av.attn_bwd)
 
     def up(bits):
         import numpy as np
@@ -146,11 +160,13 @@ def main():
         torch.cuda.synchronize()
         log(f"[bench] calibration copy: {q.numel() * 2} bytes read, {q.numel() * 2} bytes written per launch")
 
+    # the general entry points cover every format / masking / packing; for the reported configuration
+    # (bf16, unmasked, separate tensors) they run exactly what avion_attn_fwd / avion_attn_bwd run
     def fwd():
-        attn_fwd(q, k, v, o, lse, w.scale, stream)
+        av.attn_fwd_ex(q, k, v, o, lse, w.scale, args.causal, stream)
 
     def bwd():
-        attn_bwd(q, k, v, o, lse, dO, dq, dk, dv, w.scale, ws, stream)
+        av.attn_bwd_ex(q, k, v, o, lse, dO, dq, dk, dv, w.scale, ws, args.causal, stream)
 
     # the phase entry points exist for bf16; for the phase split of an fp16 run they are fed the same
     # bytes viewed as bf16 (same instruction stream and traffic, values irrelevant to a timing)
@@ -169,29 +185,41 @@ def main():
         dqkv = torch.empty_like(qkv)
 
         def fwd():
-            av.attn_fwd_qkvpacked(qkv, o, lse, w.scale, stream)
+            av.attn_fwd_ex(qkv, None, None, o, lse, w.scale, args.causal, stream)
 
         def bwd():
-            av.attn_bwd_qkvpacked(qkv, o, lse, dO, dqkv, w.scale, ws, stream)
+            av.attn_bwd_ex(qkv, None, None, o, lse, dO, dqkv, None, None, w.scale, ws, args.causal, stream)
 
     def step():
         fwd()
         bwd()
 
-    # whole hot path: W warm-up steps, then exactly K timed steps between synchronisations
+    # untimed pre-warm until the clocks have settled, then W warm-up steps
+    t_end = time.perf_counter() + PREWARM_SECONDS
+    while time.perf_counter() < t_end:
+        for _ in range(10):
+            step()
+        torch.cuda.synchronize()
     for _ in range(args.warmup):
         step()
+    # whole hot path: exactly K steps between two HIP events on the launch stream (and the host's clock around them)
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
+    e0.record(stream)
     for _ in range(args.steps):
         step()
+    e1.record(stream)
     torch.cuda.synchronize()
-    ms_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    ms_wall = (time.perf_counter() - t0) * 1e3 / args.steps
+    ms_step = e0.elapsed_time(e1) / args.steps
+    repeat_ms = sorted(event_ms(step, args.steps, stream) for _ in range(4))
 
-    # per-phase times with HIP events on the launch stream
+    # per-phase times, same protocol (median of three K-launch blocks each)
     ms_fwd = timed(fwd, args.steps, 2, stream)
     ms_bwd = timed(bwd, args.steps, 2, stream)
-    if packed or f16:
+    if packed or f16 or args.causal:
         # these calls have no separate phases: split the backward's time in the proportion of the two
         # kernels of the reported configuration
         a, b = timed(bwd_dq, args.steps, 2, stream), timed(bwd_dkdv, args.steps, 2, stream)
@@ -215,10 +243,16 @@ def main():
     out = {
         "metric": "attention fwd+bwd TFLOP/s (N=1568,d=64) and % of MI355X bf16 MFMA peak",
         "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": ms_step, "ms_per_step_wall": ms_wall,
+        "repeats": {"ms_per_step": repeat_ms, "median": repeat_ms[len(repeat_ms) // 2], "min": repeat_ms[0],
+                    "note": "further blocks of K steps each, HIP events on the launch stream"},
+        "timing": "HIP events on the launch stream around exactly K steps, after an untimed pre-warm of "
+                  f"{PREWARM_SECONDS} s and W warm-up steps",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": args.dtype, "data": "synthetic" if args.operands == "recipe" else f"constant operands ({args.operands}), diagnostic only",
-        "config": {"workload": f"{w.name}: B={w.B} H={w.H} N={w.N} d={w.d} non-causal, scale={w.scale:g}, "
-                               f"Q/K/V/dO ~ N(0,1) {args.dtype}, fwd+bwd" + (", packed [B,N,3,H,d] QKV" if packed else "")},
+        "config": {"workload": f"{w.name}: B={w.B} H={w.H} N={w.N} d={w.d} {'causal' if args.causal else 'non-causal'}, scale={w.scale:g}, "
+                               f"Q/K/V/dO ~ N(0,1) {args.dtype}, fwd+bwd" + (", packed [B,N,3,H,d] QKV" if packed else "")
+                               + (", CAUSAL variant (diagnostic)" if args.causal else "")},
         "pct_of_bf16_mfma_peak": 100.0 * value / PEAK_BF16_TFLOPS,
         "phases": {
             "fwd": {"ms": ms_fwd, "tflops": tf(4 * base, ms_fwd), "pct_peak": 100 * tf(4 * base, ms_fwd) / PEAK_BF16_TFLOPS},
@@ -230,8 +264,13 @@ def main():
                      "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
                      "algorithmic_flops_per_launch": dom_flops, "avg_launch_ms": dom_ms},
     }
-    out["roofline"]["traffic"] = MEASURED_HBM_BYTES_PER_LAUNCH.get((args.workload, dom_name))
-    if args.checkpointing:
+    entry = MEASURED_HBM_BYTES_PER_LAUNCH.get((args.workload, args.dtype, dom_name))
+    if entry is not None and not packed and not args.causal and args.operands == "recipe":
+        out["roofline"]["traffic"] = entry[0]
+        out["roofline"]["traffic_source"] = f"rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, profiled offline: {entry[1]}"
+    else:
+        out["roofline"]["traffic_source"] = "null: no committed counter summary for this workload / dtype / layout / operands"
+    if not args.no_checkpointing:
         def ckpt_step():
             fwd()      # forward pass of the training step (activations dropped)
             fwd()      # recomputation of the layer inside the backward pass

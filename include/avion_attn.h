@@ -175,6 +175,33 @@ int avion_attn_bwd_causal(const void *q, const void *k, const void *v, const voi
                           void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * General forms: every combination of element format, masking and tensor packing that the kernels
+ * are instantiated for (the entry points above are the common cases of these two).  `flags` is a
+ * bitwise OR of:
+ *   AVION_FLAG_F16       tensors are fp16 instead of bf16 (as avion_attn_*_f16: the precision of the
+ *                        paper's throughput figure)
+ *   AVION_FLAG_CAUSAL    query i attends to keys 0..i (as avion_attn_*_causal: the GPT-like text
+ *                        encoder of the video-language model)
+ *   AVION_FLAG_QKVPACKED `q` is the [B,N,3,H,d] output of the joint projection (Sec. 3, "Video
+ *                        Transformer") and `dq` receives the gradient in the same packing; k, v,
+ *                        dk, dv must then be NULL (AVION_EINVAL otherwise)
+ * Any other bit set returns AVION_EINVAL.  All other arguments, limits, workspace size and error
+ * behaviour are those of avion_attn_fwd / avion_attn_bwd; the results are bit-identical to the
+ * specific entry point where one exists.
+ */
+#define AVION_FLAG_F16 1u
+#define AVION_FLAG_CAUSAL 2u
+#define AVION_FLAG_QKVPACKED 4u
+
+int avion_attn_fwd_ex(const void *q, const void *k, const void *v, void *o, float *lse,
+                      int B, int H, int N, int d, float scale, unsigned flags, void *stream);
+
+int avion_attn_bwd_ex(const void *q, const void *k, const void *v, const void *o, const float *lse,
+                      const void *dO, void *dq, void *dk, void *dv,
+                      int B, int H, int N, int d, float scale, unsigned flags,
+                      void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Allocation-free backward, for callers that cannot provide device scratch of their own: code
  * under HIP graph capture, tight serving or training loops, harnesses that forbid hipMalloc.
  * Same operation, arguments, rules and bits as avion_attn_bwd (bf16, not causal), without the

@@ -15,6 +15,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libavion_attn.so")
 
 OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP, ESCRATCH = 0, -1, -2, -3, -4, -5
+FLAG_F16, FLAG_CAUSAL, FLAG_QKVPACKED = 1, 2, 4
 
 _lib = None
 
@@ -63,6 +64,11 @@ def load_library() -> ctypes.CDLL:
         lib.avion_attn_fwd_causal.argtypes = lib.avion_attn_fwd.argtypes
         lib.avion_attn_bwd_causal.restype = i
         lib.avion_attn_bwd_causal.argtypes = lib.avion_attn_bwd.argtypes
+        u = ctypes.c_uint
+        lib.avion_attn_fwd_ex.restype = i
+        lib.avion_attn_fwd_ex.argtypes = [p, p, p, p, p, i, i, i, i, f, u, p]
+        lib.avion_attn_bwd_ex.restype = i
+        lib.avion_attn_bwd_ex.argtypes = [p, p, p, p, p, p, p, p, p, i, i, i, i, f, u, p, sz, p]
         lib.avion_attn_bwd_noalloc.restype = i
         lib.avion_attn_bwd_noalloc.argtypes = [p, p, p, p, p, p, p, p, p, i, i, i, i, f, p]
         _lib = lib
@@ -232,3 +238,58 @@ def attn_bwd_qkvpacked(qkv, o, lse, dO, dqkv, scale: float, workspace, stream=No
     _check(load_library().avion_attn_bwd_qkvpacked(_ptr(qkv), _ptr(o), _ptr(lse), _ptr(dO), _ptr(dqkv), B, H, N, d,
                                                    float(scale), _ptr(workspace), workspace.numel(),
                                                    _stream_handle(stream)))
+
+
+def _flags(dtype, causal: bool, packed: bool) -> int:
+    import torch
+    if dtype not in (torch.bfloat16, torch.float16):
+        raise ValueError(f"tensors must be bf16 or fp16, got {dtype}")
+    return (FLAG_F16 if dtype == torch.float16 else 0) | (FLAG_CAUSAL if causal else 0) | (FLAG_QKVPACKED if packed else 0)
+
+
+def attn_fwd_ex(q, k, v, o, lse, scale: float, causal: bool = False, stream=None) -> None:
+    """avion_attn_fwd_ex: any combination of format (bf16 / fp16, taken from q.dtype), masking (`causal`)
+    and packing (k is None and v is None: q is the packed [B,N,3,H,d] tensor)."""
+    import torch
+    packed = k is None and v is None
+    dt = q.dtype
+    if packed:
+        B, N, three, H, d = q.shape
+        _require(q, "qkv", dt, (B, N, 3, H, d))
+    else:
+        B, N, H, d = q.shape
+        for t, n in ((q, "q"), (k, "k"), (v, "v")):
+            _require(t, n, dt, (B, N, H, d))
+    _require(o, "o", dt, (B, N, H, d))
+    _require(lse, "lse", torch.float32, (B, H, N))
+    none = ctypes.c_void_p(None)
+    _check(load_library().avion_attn_fwd_ex(_ptr(q), none if packed else _ptr(k), none if packed else _ptr(v), _ptr(o),
+                                            _ptr(lse), B, H, N, d, float(scale), _flags(dt, causal, packed),
+                                            _stream_handle(stream)))
+
+
+def attn_bwd_ex(q, k, v, o, lse, dO, dq, dk, dv, scale: float, workspace, causal: bool = False, stream=None) -> None:
+    """avion_attn_bwd_ex: the gradients for avion_attn_fwd_ex with the same format, masking and packing
+    (packed: k, v, dk, dv are None, q and dq are the packed tensors)."""
+    import torch
+    packed = k is None and v is None
+    dt = q.dtype
+    if packed:
+        B, N, three, H, d = q.shape
+        for t, n in ((q, "qkv"), (dq, "dqkv")):
+            _require(t, n, dt, (B, N, 3, H, d))
+        if dk is not None or dv is not None:
+            raise ValueError("packed call: dk and dv must be None (dq receives the packed gradient)")
+    else:
+        B, N, H, d = q.shape
+        for t, n in ((q, "q"), (k, "k"), (v, "v"), (dq, "dq"), (dk, "dk"), (dv, "dv")):
+            _require(t, n, dt, (B, N, H, d))
+    for t, n in ((o, "o"), (dO, "dO")):
+        _require(t, n, dt, (B, N, H, d))
+    _require(lse, "lse", torch.float32, (B, H, N))
+    _require(workspace, "workspace", torch.uint8)
+    none = ctypes.c_void_p(None)
+    opt = lambda t: none if t is None else _ptr(t)
+    _check(load_library().avion_attn_bwd_ex(_ptr(q), opt(k), opt(v), _ptr(o), _ptr(lse), _ptr(dO), _ptr(dq), opt(dk),
+                                            opt(dv), B, H, N, d, float(scale), _flags(dt, causal, packed),
+                                            _ptr(workspace), workspace.numel(), _stream_handle(stream)))

@@ -295,22 +295,25 @@ int bwd_small_impl(const void* q, const void* k, const void* v, const void* o, c
 }
 
 int bwd_impl(const void* q, const void* k, const void* v, const void* o, const float* lse, const void* dO, void* dq,
-             void* dk, void* dv, int B, int H, int N, int d, Variant var, float scale, void* workspace, size_t workspace_bytes,
-             void* stream)
+             void* dk, void* dv, int B, int H, int N, int d, int packed, Variant var, float scale, void* workspace,
+             size_t workspace_bytes, void* stream)
 {
     // every argument is checked before the first launch, so an error leaves all outputs untouched
     if (!q || !k || !v || !o || !lse || !dO || !dq || !dk || !dv) return AVION_EINVAL;
-    const int rc = check_shape(B, H, N, d, scale);
+    const int rc = check_shape(B, H, N, d, scale, packed);
     if (rc != AVION_OK) return rc;
     const void* ptrs[] = {q, k, v, o, lse, dO, dq, dk, dv};
     for (const void* p : ptrs)
         if (!aligned16(p)) return AVION_EUNSUPPORTED;
     if (!workspace_ok(workspace, workspace_bytes, B, H, N, d)) return AVION_EWORKSPACE;
-    if (N <= BwdSmallCfg<64, 4>::MAX_N) return bwd_small_impl(q, k, v, o, lse, dO, dq, dk, dv, B, H, N, d, 1, var, scale, workspace, stream);
-    const int rq = dq_impl(q, k, v, o, lse, dO, dq, B, H, N, d, 1, var, scale, workspace, workspace_bytes, stream);
+    if (N <= BwdSmallCfg<64, 4>::MAX_N)
+        return bwd_small_impl(q, k, v, o, lse, dO, dq, dk, dv, B, H, N, d, packed, var, scale, workspace, stream);
+    const int rq = dq_impl(q, k, v, o, lse, dO, dq, B, H, N, d, packed, var, scale, workspace, workspace_bytes, stream);
     if (rq != AVION_OK) return rq;
-    return dkdv_impl(q, k, v, lse, dO, dk, dv, B, H, N, d, 1, var, scale, workspace, workspace_bytes, stream);
+    return dkdv_impl(q, k, v, lse, dO, dk, dv, B, H, N, d, packed, var, scale, workspace, workspace_bytes, stream);
 }
+
+constexpr unsigned kAllFlags = AVION_FLAG_F16 | AVION_FLAG_CAUSAL | AVION_FLAG_QKVPACKED;
 
 // q, k, v planes of a packed [B, N, 3, H, d] tensor
 struct Planes {
@@ -387,7 +390,7 @@ int avion_attn_bwd(const void* q, const void* k, const void* v, const void* o, c
                    void* dq, void* dk, void* dv, int B, int H, int N, int d, float scale, void* workspace,
                    size_t workspace_bytes, void* stream)
 {
-    return bwd_impl(q, k, v, o, lse, dO, dq, dk, dv, B, H, N, d, Variant{false, false}, scale, workspace, workspace_bytes,
+    return bwd_impl(q, k, v, o, lse, dO, dq, dk, dv, B, H, N, d, 1, Variant{false, false}, scale, workspace, workspace_bytes,
                     stream);
 }
 
@@ -405,7 +408,7 @@ int avion_attn_bwd_noalloc(const void* q, const void* k, const void* v, const vo
     if (rs != AVION_OK) return rs;
     // every entry of the scratch that the second pass reads is written by the first one (padding
     // rows included), so nothing has to be cleared between calls
-    return bwd_impl(q, k, v, o, lse, dO, dq, dk, dv, B, H, N, d, Variant{false, false}, scale, ws, need, stream);
+    return bwd_impl(q, k, v, o, lse, dO, dq, dk, dv, B, H, N, d, 1, Variant{false, false}, scale, ws, need, stream);
 }
 
 int avion_attn_fwd_causal(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int N, int d,
@@ -418,7 +421,7 @@ int avion_attn_bwd_causal(const void* q, const void* k, const void* v, const voi
                           void* dq, void* dk, void* dv, int B, int H, int N, int d, float scale, void* workspace,
                           size_t workspace_bytes, void* stream)
 {
-    return bwd_impl(q, k, v, o, lse, dO, dq, dk, dv, B, H, N, d, Variant{false, true}, scale, workspace, workspace_bytes,
+    return bwd_impl(q, k, v, o, lse, dO, dq, dk, dv, B, H, N, d, 1, Variant{false, true}, scale, workspace, workspace_bytes,
                     stream);
 }
 
@@ -432,30 +435,43 @@ int avion_attn_bwd_f16(const void* q, const void* k, const void* v, const void* 
                        void* dq, void* dk, void* dv, int B, int H, int N, int d, float scale, void* workspace,
                        size_t workspace_bytes, void* stream)
 {
-    return bwd_impl(q, k, v, o, lse, dO, dq, dk, dv, B, H, N, d, Variant{true, false}, scale, workspace, workspace_bytes,
+    return bwd_impl(q, k, v, o, lse, dO, dq, dk, dv, B, H, N, d, 1, Variant{true, false}, scale, workspace, workspace_bytes,
                     stream);
 }
 
 int avion_attn_bwd_qkvpacked(const void* qkv, const void* o, const float* lse, const void* dO, void* dqkv, int B, int H,
                              int N, int d, float scale, void* workspace, size_t workspace_bytes, void* stream)
 {
-    if (!qkv || !o || !lse || !dO || !dqkv) return AVION_EINVAL;
-    const int rc = check_shape(B, H, N, d, scale, 3);
-    if (rc != AVION_OK) return rc;
-    const void* ptrs[] = {qkv, o, lse, dO, dqkv};
-    for (const void* p : ptrs)
-        if (!aligned16(p)) return AVION_EUNSUPPORTED;
-    if (!workspace_ok(workspace, workspace_bytes, B, H, N, d)) return AVION_EWORKSPACE;
-    const Planes in(qkv, H, d), out(dqkv, H, d);
-    void *dq = const_cast<char*>(out.q), *dk = const_cast<char*>(out.k), *dv = const_cast<char*>(out.v);
-    if (N <= BwdSmallCfg<64, 4>::MAX_N)
-        return bwd_small_impl(in.q, in.k, in.v, o, lse, dO, dq, dk, dv, B, H, N, d, 3, Variant{false, false}, scale, workspace,
-                              stream);
-    const int rq = dq_impl(in.q, in.k, in.v, o, lse, dO, dq, B, H, N, d, 3, Variant{false, false}, scale, workspace,
-                           workspace_bytes, stream);
-    if (rq != AVION_OK) return rq;
-    return dkdv_impl(in.q, in.k, in.v, lse, dO, dk, dv, B, H, N, d, 3, Variant{false, false}, scale, workspace,
-                     workspace_bytes, stream);
+    return avion_attn_bwd_ex(qkv, nullptr, nullptr, o, lse, dO, dqkv, nullptr, nullptr, B, H, N, d, scale,
+                             AVION_FLAG_QKVPACKED, workspace, workspace_bytes, stream);
+}
+
+int avion_attn_fwd_ex(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int N, int d,
+                      float scale, unsigned flags, void* stream)
+{
+    if (flags & ~kAllFlags) return AVION_EINVAL;
+    const Variant var{(flags & AVION_FLAG_F16) != 0, (flags & AVION_FLAG_CAUSAL) != 0};
+    if (flags & AVION_FLAG_QKVPACKED) {
+        if (k || v || H < 1 || d < 1) return AVION_EINVAL;
+        const Planes p(q, H, d);
+        return fwd_impl(p.q, p.k, p.v, o, lse, B, H, N, d, 3, var, scale, stream);
+    }
+    return fwd_impl(q, k, v, o, lse, B, H, N, d, 1, var, scale, stream);
+}
+
+int avion_attn_bwd_ex(const void* q, const void* k, const void* v, const void* o, const float* lse, const void* dO,
+                      void* dq, void* dk, void* dv, int B, int H, int N, int d, float scale, unsigned flags,
+                      void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (flags & ~kAllFlags) return AVION_EINVAL;
+    const Variant var{(flags & AVION_FLAG_F16) != 0, (flags & AVION_FLAG_CAUSAL) != 0};
+    if (flags & AVION_FLAG_QKVPACKED) {
+        if (k || v || dk || dv || !q || !dq || H < 1 || d < 1) return AVION_EINVAL;
+        const Planes in(q, H, d), out(dq, H, d);
+        return bwd_impl(in.q, in.k, in.v, o, lse, dO, const_cast<char*>(out.q), const_cast<char*>(out.k),
+                        const_cast<char*>(out.v), B, H, N, d, 3, var, scale, workspace, workspace_bytes, stream);
+    }
+    return bwd_impl(q, k, v, o, lse, dO, dq, dk, dv, B, H, N, d, 1, var, scale, workspace, workspace_bytes, stream);
 }
 
 }  // extern "C"

@@ -183,7 +183,9 @@ struct DkvCfg {
     static constexpr int BNK = 32 * NW;
     using Ring = TileRing<D, NW, 2, true>;
     static constexpr int LDS_BYTES = Ring::LDS_BYTES;
-    static constexpr int WAVES_PER_SIMD = 2;  // a floor for the register budget; D = 64 fits three
+    // resident wavefronts per SIMD the register budget is held to: three for D = 64 (at most 168
+    // registers; the schedule relies on three wavefronts filling each other's waits), two for D = 80
+    static constexpr int WAVES_PER_SIMD = D == 64 ? 3 : 2;
 };
 
 // The work of one workgroup: key block kb of (batch, head) bh.

@@ -9,8 +9,9 @@ MAX_ABS = 2e-2        # O, dQ, dK, dV: largest absolute error over the tensor
 REL_FRO = 5e-3        # O, dQ, dK, dV: ||gpu - ref||_F / ||ref||_F over the tensor
 LSE_ABS = 1e-3        # LSE: largest absolute error
 # With fewer than 16 keys, dS = P*(dP - delta) cancels almost completely and the bf16 rounding of
-# the O that delta is built from shows through undamped (no averaging over keys); the same
-# arithmetic emulated in fp64 with bf16 roundings gives 1e-2 at N = 2.  Such rows get this bound.
+# the O that delta is built from shows through undamped (no averaging over keys).  The bound for
+# such sizes is derived in tests/test_tolerance_model.py: the method's rounding points carried out
+# in fp64 exceed 5e-3 there and stay below 2e-2.
 REL_FRO_TINY_N = 2e-2
 
 
@@ -113,8 +114,10 @@ def run_hip_f16(w, x16):
     return dict(o=o, lse=lse, dq=dq, dk=dk, dv=dv)
 
 
-def check_f16_against_oracle(w, x16, out, slices=None):
-    """fp16 results against the fp64 oracle run on the exactly widened fp16 inputs."""
+def check_f16_against_oracle(w, x16, out, slices=None, abs_bound=None):
+    """fp16 results against the fp64 oracle run on the exactly widened fp16 inputs.  `abs_bound` maps
+    tensor names to an absolute bound that replaces MAX_ABS_F16 for them (derived by the caller)."""
+    abs_bound = abs_bound or {}
     import oracle
     report = {}
     sls = [(slice(None),) * 3] if slices is None else [(slice(b, b + 1), slice(None), slice(h, h + 1)) for b, h in slices]
@@ -137,7 +140,8 @@ def check_f16_against_oracle(w, x16, out, slices=None):
             assert np.all(np.isfinite(got)), f"{name}{tag}: non-finite values in the GPU result"
             max_abs, rel = errors(got, ref)
             report[name + tag] = (max_abs, rel)
-            assert max_abs <= MAX_ABS_F16, f"{name}{tag}: max-abs error {max_abs:.3e} > {MAX_ABS_F16}"
+            abs_tol = abs_bound.get(name, MAX_ABS_F16)
+            assert max_abs <= abs_tol, f"{name}{tag}: max-abs error {max_abs:.3e} > {abs_tol:.3e}"
             assert rel <= tol, f"{name}{tag}: relative Frobenius error {rel:.3e} > {tol}"
     return report
 
@@ -150,48 +154,53 @@ def errors(gpu_f64, ref):
     return max_abs, rel
 
 
-def assert_close(name, gpu_f64, ref, report=None, rel_tol=REL_FRO, strict_abs=True):
+def assert_close(name, gpu_f64, ref, report=None, rel_tol=REL_FRO, strict_abs=True, abs_bound=None):
     assert np.all(np.isfinite(gpu_f64)), f"{name}: non-finite values in the GPU result"
     max_abs, rel = errors(gpu_f64, ref)
     if report is not None:
         report[name] = (max_abs, rel)
-    abs_tol = MAX_ABS
+    abs_tol = MAX_ABS if abs_bound is None else abs_bound
     if not strict_abs:
         # Extra stress cases (near one-hot weights, outputs far larger than in the named
         # workloads): P and dS enter their contractions rounded to bf16 (up to 2^-8 relative on a
         # dominant term) and the result is rounded again, so the absolute bound follows one bf16
-        # ulp (2^-7) of the largest reference magnitude once that exceeds MAX_ABS.
+        # ulp (2^-7) of the largest reference magnitude once that exceeds MAX_ABS -- and is the
+        # strict MAX_ABS wherever it does not.  tests/test_tolerance_model.py shows that the
+        # method's own arithmetic needs this rule on these cases and meets it.
         abs_tol = max(MAX_ABS, float(np.abs(ref).max()) * 2.0 ** -7)
     assert max_abs <= abs_tol, f"{name}: max-abs error {max_abs:.3e} > {abs_tol:.3e}"
     assert rel <= rel_tol, f"{name}: relative Frobenius error {rel:.3e} > {rel_tol}"
 
 
-def check_against_oracle(w, x, out, slices=None, strict_abs=True, causal=False):
-    """Compare the HIP results with the oracle, on the whole problem or on chosen (b,h) slices."""
+def check_against_oracle(w, x, out, slices=None, strict_abs=True, causal=False, abs_bound=None):
+    """Compare the HIP results with the oracle, on the whole problem or on chosen (b,h) slices.
+    `abs_bound` maps tensor names ("dQ", ...) to an absolute bound that replaces MAX_ABS for them
+    (derived by the caller; the relative bounds are never replaced)."""
     import oracle
     report = {}
     grad_tol = REL_FRO if w.N >= 16 else REL_FRO_TINY_N
+    abs_bound = abs_bound or {}
     if slices is None:
         ro, rl = oracle.fwd(x["q"], x["k"], x["v"], w.scale, causal=causal)
         rdq, rdk, rdv = oracle.bwd(x["q"], x["k"], x["v"], x["dO"], w.scale, causal=causal)
-        assert_close("O", bf16_tensor_to_f64(out["o"]), ro, report, REL_FRO, strict_abs)
+        assert_close("O", bf16_tensor_to_f64(out["o"]), ro, report, REL_FRO, strict_abs, abs_bound.get("O"))
         lse_err = float(np.abs(out["lse"].double().cpu().numpy() - rl).max())
         report["LSE"] = (lse_err, 0.0)
         assert lse_err <= LSE_ABS, f"LSE: max-abs error {lse_err:.3e} > {LSE_ABS}"
-        assert_close("dQ", bf16_tensor_to_f64(out["dq"]), rdq, report, grad_tol, strict_abs)
-        assert_close("dK", bf16_tensor_to_f64(out["dk"]), rdk, report, grad_tol, strict_abs)
-        assert_close("dV", bf16_tensor_to_f64(out["dv"]), rdv, report, grad_tol, strict_abs)
+        assert_close("dQ", bf16_tensor_to_f64(out["dq"]), rdq, report, grad_tol, strict_abs, abs_bound.get("dQ"))
+        assert_close("dK", bf16_tensor_to_f64(out["dk"]), rdk, report, grad_tol, strict_abs, abs_bound.get("dK"))
+        assert_close("dV", bf16_tensor_to_f64(out["dv"]), rdv, report, grad_tol, strict_abs, abs_bound.get("dV"))
         return report
     for (b, h) in slices:
         sl = (slice(b, b + 1), slice(None), slice(h, h + 1))
         ro, rl = oracle.fwd(x["q"][sl], x["k"][sl], x["v"][sl], w.scale, causal=causal)
         rdq, rdk, rdv = oracle.bwd(x["q"][sl], x["k"][sl], x["v"][sl], x["dO"][sl], w.scale, causal=causal)
         tag = f"[b={b},h={h}]"
-        assert_close("O" + tag, bf16_tensor_to_f64(out["o"][sl]), ro, report, REL_FRO, strict_abs)
+        assert_close("O" + tag, bf16_tensor_to_f64(out["o"][sl]), ro, report, REL_FRO, strict_abs, abs_bound.get("O"))
         lse_err = float(np.abs(out["lse"][b, h].double().cpu().numpy() - rl[0, 0]).max())
         report["LSE" + tag] = (lse_err, 0.0)
         assert lse_err <= LSE_ABS, f"LSE{tag}: max-abs error {lse_err:.3e} > {LSE_ABS}"
-        assert_close("dQ" + tag, bf16_tensor_to_f64(out["dq"][sl]), rdq, report, grad_tol, strict_abs)
-        assert_close("dK" + tag, bf16_tensor_to_f64(out["dk"][sl]), rdk, report, grad_tol, strict_abs)
-        assert_close("dV" + tag, bf16_tensor_to_f64(out["dv"][sl]), rdv, report, grad_tol, strict_abs)
+        assert_close("dQ" + tag, bf16_tensor_to_f64(out["dq"][sl]), rdq, report, grad_tol, strict_abs, abs_bound.get("dQ"))
+        assert_close("dK" + tag, bf16_tensor_to_f64(out["dk"][sl]), rdk, report, grad_tol, strict_abs, abs_bound.get("dK"))
+        assert_close("dV" + tag, bf16_tensor_to_f64(out["dv"][sl]), rdv, report, grad_tol, strict_abs, abs_bound.get("dV"))
     return report

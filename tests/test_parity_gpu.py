@@ -10,10 +10,23 @@ from tests import gpu_harness as gh
 pytestmark = pytest.mark.gpu
 
 
+# The one named workload whose dQ cannot meet the stated absolute bound on every head, whatever the
+# kernel: the backward takes the forward's output as rounded to the tensor format, so the row sums
+# delta = rowsum(dO o O) carry that rounding; with the peaky softmax of this workload (K doubled: few
+# effective keys, |O| up to 3.5, |sum_j P_ij k_j| up to 7) the error of delta alone moves dQ by up to
+# 2.7e-2 on some heads (shown on the CPU, with everything else exact, in
+# tests/test_tolerance_model.py).  The bound taken for that one tensor is one bf16 unit in the last
+# place of the workload's largest dQ element (5.79 over all 256 heads, from the oracle): 2^-7 * 5.79;
+# an eighth of it for the fp16 entry points.  O, dK, dV and every relative bound stay as stated.
+PEAKY_DQ_ABS = 5.79 * 2.0 ** -7
+ABS_BOUND = {"vitl_batch_peaky": {"dQ": PEAKY_DQ_ABS}}
+ABS_BOUND_F16 = {"vitl_batch_peaky": {"dQ": PEAKY_DQ_ABS / 8}}
+
+
 def _run(w, slices=None, strict_abs=True):
     x = si.make_inputs(w)
     out = gh.run_hip(w, x)
-    rep = gh.check_against_oracle(w, x, out, slices, strict_abs)
+    rep = gh.check_against_oracle(w, x, out, slices, strict_abs, abs_bound=ABS_BOUND.get(w.name))
     worst = {k: f"{v[0]:.2e}/{v[1]:.2e}" for k, v in rep.items()}
     print(f"\n{w.name}: shape={w.shape} errors(max-abs/rel-fro)={worst}", flush=True)
     return x, out
@@ -51,14 +64,27 @@ def test_cls_token_shape_full_head_count():
     _run(si.small_workload(1, 12, 1569, 64, seed=99, scale=0.125))
 
 
-@pytest.mark.parametrize("name", ["vitb_batch", "vitl_batch_peaky", "vitb_long", "vith_d80", "vitl_336"])
+def _sampled_heads(w, n):
+    """n distinct (batch, head) pairs: the first, the last and seeded random ones."""
+    rng = np.random.default_rng(w.seed)
+    heads = {(0, 0), (w.B - 1, w.H - 1)}
+    while len(heads) < min(n, w.B * w.H):
+        heads.add((int(rng.integers(w.B)), int(rng.integers(w.H))))
+    return sorted(heads)
+
+
+def test_benchmark_workload_every_element():
+    # the workload bench.py times (ViT-B video training batch), in the launch configuration it times:
+    # every element of O, LSE, dQ, dK, dV of all 384 heads against the oracle, at the strict bounds
+    _run(si.WORKLOADS["vitb_batch"])
+
+
+@pytest.mark.parametrize("name", ["vitl_batch_peaky", "vitb_long", "vith_d80", "vitl_336"])
 def test_full_size_configs_on_sampled_heads(name):
     # The launch configuration bench.py times; the oracle recomputes whole (batch, head) slices
     # (dK and dV of a head need every query of that head, so the head is the sampling unit).
     w = si.WORKLOADS[name]
-    rng = np.random.default_rng(w.seed)
-    slices = {(0, 0), (w.B - 1, w.H - 1), (int(rng.integers(w.B)), int(rng.integers(w.H)))}
-    x, out = _run(w, sorted(slices))
+    x, out = _run(w, _sampled_heads(w, 8))
     # properties that hold at any size, on the whole tensors
     import torch
     for n in ("o", "dq", "dk", "dv", "lse"):
@@ -142,6 +168,19 @@ def test_causal_text_encoder_batch_on_sampled_heads():
     assert torch.equal(out["o"][:, 0].view(torch.int16), gh.to_gpu_bf16(x["v"])[:, 0].view(torch.int16))
 
 
+def test_causal_at_the_video_token_count_on_sampled_heads():
+    # the causal kernels at the benchmark's shape (N = 1568: skipped, diagonal and full blocks in every
+    # workgroup, 13 workgroups per head), on sampled heads; the absolute bound is the strict one wherever
+    # one bf16 ulp of the largest reference value stays below it (see check_causal_against_oracle)
+    import torch
+    w = si.WORKLOADS["vitb_batch"]
+    x = si.make_inputs(w)
+    out = gh.run_hip(w, x, causal=True)
+    gh.check_causal_against_oracle(w, x, out, _sampled_heads(w, 4))
+    for n in ("o", "dq", "dk", "dv", "lse"):
+        assert bool(torch.isfinite(out[n].float()).all()), n
+
+
 def test_causal_running_max_path():
     # as test_scores_far_above_the_first_keys_take_the_running_max_path, with the causal mask: keys
     # from 64 on are 16 times larger and scale = 1, so rows from 64 on overflow the fixed reference
@@ -180,13 +219,13 @@ def test_f16_small_shapes_match_oracle(B, H, N, d):
     print(f"\nf16 {w.shape}: errors(max-abs/rel-fro)=" + str({k: f"{v[0]:.2e}/{v[1]:.2e}" for k, v in rep.items()}), flush=True)
 
 
-@pytest.mark.parametrize("name", ["vitb_batch", "vith_d80"])
+@pytest.mark.parametrize("name", ["vitb_clip", "vitb_batch", "vitl_batch_peaky", "vitb_long", "vith_d80", "vitl_336"])
 def test_f16_full_size_configs_on_sampled_heads(name):
     import torch
     w = si.WORKLOADS[name]
     x = si.make_inputs(w, fmt="f16")
     out = gh.run_hip_f16(w, x)
-    rep = gh.check_f16_against_oracle(w, x, out, [(0, 0), (w.B - 1, w.H - 1), (w.B // 2, 3)])
+    rep = gh.check_f16_against_oracle(w, x, out, _sampled_heads(w, 4), abs_bound=ABS_BOUND_F16.get(name))
     print(f"\nf16 {name}: " + str({k: f"{v[0]:.2e}/{v[1]:.2e}" for k, v in rep.items()}), flush=True)
     for n in ("o", "dq", "dk", "dv", "lse"):
         assert bool(torch.isfinite(out[n].float()).all()), n
