@@ -94,9 +94,14 @@ int avion_attn_bwd(const void *q, const void *k, const void *v, const void *o, c
 
 /*
  * The two phases of avion_attn_bwd, callable on their own (same argument rules as above).
- * avion_attn_bwd(...) gives exactly the bits of avion_attn_bwd_dq(...) followed by
+ * For N > 32, avion_attn_bwd(...) gives exactly the bits of avion_attn_bwd_dq(...) followed by
  * avion_attn_bwd_dkdv(...) on the same stream with the same workspace; for N <= 128 it runs both
  * phases in one launch (one workgroup then covers a whole (batch, head)), otherwise as two.
+ * Sequences of at most 32 tokens (temporal attention over a few frames, Sec. 4.1; very short
+ * captions) take another route in avion_attn_fwd / avion_attn_bwd and all their variants: one
+ * wavefront computes a window of floor(32 / N) whole problems at once, forward and backward each
+ * in one pass with no workspace traffic; same formulas and rounding points, another summation
+ * order, so those results agree with the two phases within the tolerances, not bit for bit.
  *
  *   avion_attn_bwd_dq   : query-stationary pass.  Computes the row sums delta = rowsum(dO o O) and
  *                         dQ = scale * (P o (dO V^T - delta)) K.  Writes dq (fully) and leaves

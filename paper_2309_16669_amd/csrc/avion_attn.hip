@@ -14,6 +14,7 @@
 
 #include "avion_bwd.h"
 #include "avion_fwd.h"
+#include "avion_small.h"
 
 // Built-in scratch of avion_attn_bwd_noalloc: the per-query scalars that the backward's two passes
 // hand to each other live here instead of in a caller's workspace.  One copy per GPU, held until
@@ -187,6 +188,56 @@ int launch_bwd_small(const raw16* q, const raw16* k, const raw16* v, const raw16
     return end_launch("launch avion_bwd_small_kernel");
 }
 
+// Sequences of at most 32 tokens: one wavefront per window of floor(32 / N) problems (avion_small.h).
+constexpr int kWindowMaxN = 32;
+struct WindowGrid {
+    int G, nitems;
+    unsigned grid;
+};
+template <int D>
+bool window_grid(int B, int H, int N, WindowGrid* w)
+{
+    w->G = 32 / N;
+    const long long nwin = ((long long)B + w->G - 1) / w->G, nitems = nwin * H;
+    if (nitems > 0x7fffffffLL) return false;
+    w->nitems = (int)nitems;
+    const long long wgs = (nitems + WinCfg<D>::NW - 1) / WinCfg<D>::NW;
+    w->grid = (unsigned)(wgs < 256 * 16 ? wgs : 256 * 16);  // wavefronts walk the windows with a stride
+    return true;
+}
+
+template <int D, typename E, bool CAUSAL>
+int launch_win_fwd(const raw16* q, const raw16* k, const raw16* v, raw16* o, float* lse, int B, int H, int N, Strides rs,
+                   float scale, hipStream_t st)
+{
+    using Cfg = WinCfg<D>;
+    static std::atomic<bool> lds_allowed{false};
+    const hipError_t attr = allow_lds(avion_win_fwd_kernel<D, E, CAUSAL>, Cfg::FWD_LDS_BYTES, lds_allowed);
+    if (attr != hipSuccess) return hip_fail(attr, "hipFuncSetAttribute(win_fwd)");
+    WindowGrid w;
+    if (!window_grid<D>(B, H, N, &w)) return AVION_EUNSUPPORTED;
+    begin_launch();
+    hipLaunchKernelGGL((avion_win_fwd_kernel<D, E, CAUSAL>), dim3(w.grid), dim3(Cfg::NT), Cfg::FWD_LDS_BYTES, st, q, k, v, o,
+                       lse, B, H, N, rs.qkv, rs.o, w.G, w.nitems, scale * kLog2e);
+    return end_launch("launch avion_win_fwd_kernel");
+}
+
+template <int D, typename E, bool CAUSAL>
+int launch_win_bwd(const raw16* q, const raw16* k, const raw16* v, const raw16* o, const raw16* dO, const float* lse,
+                   raw16* dq, raw16* dk, raw16* dv, int B, int H, int N, Strides rs, float scale, hipStream_t st)
+{
+    using Cfg = WinCfg<D>;
+    static std::atomic<bool> lds_allowed{false};
+    const hipError_t attr = allow_lds(avion_win_bwd_kernel<D, E, CAUSAL>, Cfg::BWD_LDS_BYTES, lds_allowed);
+    if (attr != hipSuccess) return hip_fail(attr, "hipFuncSetAttribute(win_bwd)");
+    WindowGrid w;
+    if (!window_grid<D>(B, H, N, &w)) return AVION_EUNSUPPORTED;
+    begin_launch();
+    hipLaunchKernelGGL((avion_win_bwd_kernel<D, E, CAUSAL>), dim3(w.grid), dim3(Cfg::NT), Cfg::BWD_LDS_BYTES, st, q, k, v, o,
+                       dO, lse, dq, dk, dv, B, H, N, rs.qkv, rs.o, w.G, w.nitems, scale * kLog2e, scale);
+    return end_launch("launch avion_win_bwd_kernel");
+}
+
 // Kernel instances: four wavefronts per workgroup for every kernel, head size, format and masking.
 // Calls f(head dim, element format, causal) with the three as compile-time tags.
 template <typename T>
@@ -220,6 +271,11 @@ int fwd_impl(const void* q, const void* k, const void* v, void* o, float* lse, i
     const Strides rs{packed * H * d, H * d};
     const raw16 *qq = static_cast<const raw16*>(q), *kk = static_cast<const raw16*>(k), *vv = static_cast<const raw16*>(v);
     raw16* oo = static_cast<raw16*>(o);
+    if (N <= kWindowMaxN)
+        return by_variant(var, d, [&](auto dim, auto fmt, auto causal) {
+            return launch_win_fwd<decltype(dim)::value, typename decltype(fmt)::type, decltype(causal)::value>(
+                qq, kk, vv, oo, lse, B, H, N, rs, scale, st);
+        });
     return by_variant(var, d, [&](auto dim, auto fmt, auto causal) {
         return launch_fwd<decltype(dim)::value, 4, typename decltype(fmt)::type, decltype(causal)::value>(
             qq, kk, vv, oo, lse, B, H, N, rs, scale, st);
@@ -306,6 +362,18 @@ int bwd_impl(const void* q, const void* k, const void* v, const void* o, const f
     for (const void* p : ptrs)
         if (!aligned16(p)) return AVION_EUNSUPPORTED;
     if (!workspace_ok(workspace, workspace_bytes, B, H, N, d)) return AVION_EWORKSPACE;
+    if (N <= kWindowMaxN) {
+        // one wavefront per window of problems; needs no workspace (it is still checked, as for every shape)
+        hipStream_t st = static_cast<hipStream_t>(stream);
+        const Strides rs{packed * H * d, H * d};
+        const raw16 *qq = static_cast<const raw16*>(q), *kk = static_cast<const raw16*>(k), *vv = static_cast<const raw16*>(v),
+                    *oo = static_cast<const raw16*>(o), *gg = static_cast<const raw16*>(dO);
+        raw16 *dqq = static_cast<raw16*>(dq), *dkk = static_cast<raw16*>(dk), *dvv = static_cast<raw16*>(dv);
+        return by_variant(var, d, [&](auto dim, auto fmt, auto causal) {
+            return launch_win_bwd<decltype(dim)::value, typename decltype(fmt)::type, decltype(causal)::value>(
+                qq, kk, vv, oo, gg, lse, dqq, dkk, dvv, B, H, N, rs, scale, st);
+        });
+    }
     if (N <= BwdSmallCfg<64, 4>::MAX_N)
         return bwd_small_impl(q, k, v, o, lse, dO, dq, dk, dv, B, H, N, d, packed, var, scale, workspace, stream);
     const int rq = dq_impl(q, k, v, o, lse, dO, dq, B, H, N, d, packed, var, scale, workspace, workspace_bytes, stream);

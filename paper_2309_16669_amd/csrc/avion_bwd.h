@@ -147,7 +147,7 @@ DEVINL void avion_dq_body(char* smem, const raw16* __restrict__ q, const raw16* 
 #pragma unroll
             for (int hk = 0; hk < 2; ++hk) {
                 const int key_base = t * BN + 32 * hk;
-                if (CAUSAL && key_base >= wave_key_end) continue;  // no query of this wavefront sees these keys
+                if (key_base >= wave_key_end) continue;  // past the last key, or (causal) seen by no query of this wavefront
                 if (key_base + 32 > mask_from) unit(std::true_type{}, ring.buf(t), ring.buf(t) + Ring::OFF_B, hk, key_base);
                 else unit(std::false_type{}, ring.buf(t), ring.buf(t) + Ring::OFF_B, hk, key_base);
             }
@@ -250,6 +250,7 @@ DEVINL void avion_dkdv_body(char* smem, const raw16* __restrict__ q, const raw16
                 const int query_base = t * BQ + 32 * hq;
                 // causal: units whose queries all lie before this wavefront's keys contribute nothing;
                 // units that straddle the diagonal start their scores from the mask
+                if (query_base >= N) continue;  // past the last query
                 if (CAUSAL && query_base + 32 <= k0) continue;
                 const float* rowv = reinterpret_cast<const float*>(buf + OFF_ROW) + 32 * hq + 4 * g;
                 // dP starts from -delta of the accumulator rows' queries (broadcast LDS reads)

@@ -215,7 +215,7 @@ avion_fwd_kernel(const raw16* __restrict__ q, const raw16* __restrict__ k, const
 #pragma unroll
             for (int hk = 0; hk < 2; ++hk) {
                 const int key_base = t * BN + 32 * hk;
-                if (CAUSAL && key_base >= wave_key_end) continue;  // no query of this wavefront sees these keys
+                if (key_base >= wave_key_end) continue;  // past the last key, or (causal) seen by no query of this wavefront
                 f32x16 s;
                 if (key_base + 32 > mask_from) s = scores(std::true_type{}, kt, hk, key_base);
                 else s = scores(std::false_type{}, kt, hk, key_base);

@@ -47,6 +47,41 @@ def test_small_shapes_match_oracle(B, H, N, d):
     _run(si.small_workload(B, H, N, d, seed=1000 + 7 * N + d + B))
 
 
+# Divided space/time attention (the comparison architecture of Sec. 4.1): temporal attention is one
+# problem of N = T tokens per spatial position and clip, spatial attention one of N = 14*14 per frame.
+# Sequences of at most 32 tokens run as windows of floor(32 / N) problems per wavefront.
+@pytest.mark.parametrize("T", [4, 8, 16])
+def test_temporal_attention_every_problem(T):
+    # 8 clips x 196 positions, 12 heads of 64; 196 * 8 is a multiple of every window size used here.
+    # A softmax over a handful of keys is near one-hot in many of the 18816 problems, so the absolute
+    # bound follows the one-ulp rule (as for causal rows, which are softmaxes over few keys too).
+    _run(si.small_workload(8 * 196, 12, T, 64, seed=4100 + T), strict_abs=False)
+
+
+@pytest.mark.parametrize("B,H,N,d", [(37, 3, 3, 64), (1, 1, 32, 64), (50, 2, 7, 80), (3, 2, 17, 64), (100, 1, 1, 64), (11, 4, 20, 80)])
+def test_windows_with_ragged_ends(B, H, N, d):
+    # windows that are not full (32 % N != 0), last windows with fewer problems (B % floor(32/N) != 0)
+    _run(si.small_workload(B, H, N, d, seed=4200 + 31 * B + N), strict_abs=False)
+
+
+def test_spatial_attention_on_sampled_heads():
+    # 32 clips x 8 frames as 256 problems of 14 x 14 tokens
+    w = si.small_workload(256, 12, 196, 64, seed=4300)
+    _run(w, _sampled_heads(w, 6))
+
+
+def test_window_kernels_are_bitwise_reproducible():
+    import torch
+    w = si.small_workload(301, 5, 6, 64, seed=4400)
+    x = si.make_inputs(w)
+    a = gh.run_hip(w, x)
+    for _ in range(2):
+        b = gh.run_hip(w, x)
+        for n in a:
+            assert torch.equal(a[n].view(torch.int16) if a[n].dtype == torch.bfloat16 else a[n],
+                               b[n].view(torch.int16) if b[n].dtype == torch.bfloat16 else b[n]), n
+
+
 def test_peaky_softmax_small():
     # few effective keys: gradients reach magnitudes of 10 and more, so the absolute bound
     # follows the bf16 ulp of the largest value; the relative bound is unchanged

@@ -51,16 +51,19 @@ def check(w, x, out, f16, causal):
     ro, rl = oracle.fwd_f64(q, k, v, w.scale, causal=causal)
     refs = oracle.bwd_f64(q, k, v, dO, w.scale, causal=causal)
     max_abs_tol, rel_tol, ulp = (gh.MAX_ABS_F16, gh.REL_FRO_F16, 2.0 ** -10) if f16 else (gh.MAX_ABS, gh.REL_FRO, 2.0 ** -7)
+    # fewer than 16 keys: the gradients' relative bound of tests/test_tolerance_model.py (an eighth of it in fp16)
+    grad_tol = rel_tol if w.N >= 16 else (gh.REL_FRO_TINY_N / 8 if f16 else gh.REL_FRO_TINY_N)
     assert float(np.abs(out["lse"].double().cpu().numpy() - rl).max()) <= gh.LSE_ABS
     for name, key, ref in (("O", "o", ro), ("dQ", "dq", refs[0]), ("dK", "dk", refs[1]), ("dV", "dv", refs[2])):
         got = out[key].contiguous().double().cpu().numpy()
         assert np.all(np.isfinite(got)), name
         max_abs, rel = gh.errors(got, ref)
         assert max_abs <= max(max_abs_tol, float(np.abs(ref).max()) * ulp), (name, max_abs)
-        assert rel <= rel_tol, (name, rel)
+        assert rel <= (rel_tol if name == "O" else grad_tol), (name, rel)
 
 
-SHAPES = [(2, 3, 197, 64), (3, 8, 77, 64), (1, 2, 300, 80), (1, 2, 785, 64)]
+# the last three run as windows of several problems per wavefront (N <= 32), with a ragged last window
+SHAPES = [(2, 3, 197, 64), (3, 8, 77, 64), (1, 2, 300, 80), (1, 2, 785, 64), (7, 3, 12, 64), (5, 2, 5, 80), (9, 2, 32, 64)]
 
 
 @pytest.mark.parametrize("f16,causal,packed", [c for c in itertools.product((False, True), repeat=3)])
