@@ -113,6 +113,7 @@ def main():
                     help="skip the extra timing of the step of a layer trained with gradient checkpointing "
                          "(Sec. 4.1 of the paper: the forward runs a second time before the backward), which is "
                          "reported beside the metric and does not change it")
+    ap.add_argument("--no-layernorm", action="store_true", help="skip the layer-normalisation block of the line")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain device copy of Q (known size) so that HBM counters of a "
                          "rocprofv3 --pmc run can be scaled")
@@ -280,6 +281,30 @@ def main():
             "ms_per_step": ms_ckpt, "slowdown_vs_plain_step": ms_ckpt / ms_step,
             "note": "fwd + fwd + bwd; still 14*B*H*N^2*d useful flops",
             "tflops_useful": tf(14 * base, ms_ckpt)}
+    if not args.no_layernorm:
+        # the layer's normalisation on the same tokens ([B*N, H*d], same format): bound by HBM bandwidth;
+        # algorithmic bytes: forward reads x and writes y (2 x 2 bytes per element), backward reads x and
+        # dy and writes dx (3 x 2), plus two floats per row
+        M, D = w.B * w.N, w.H * w.d
+        if D % 8 == 0 and D <= 2048:
+            xt = torch.randn((M, D), device=dev).to(q.dtype)
+            dyt = torch.randn((M, D), device=dev).to(q.dtype)
+            gam, bet = torch.ones(D, device=dev), torch.zeros(D, device=dev)
+            yt, dxt = torch.empty_like(xt), torch.empty_like(xt)
+            mu, rs = torch.empty(M, device=dev), torch.empty(M, device=dev)
+            dgam, dbet = torch.empty(D, device=dev), torch.empty(D, device=dev)
+            lws = torch.empty(av.layernorm_bwd_workspace_bytes(M, D), dtype=torch.uint8, device=dev)
+            ms_lf = timed(lambda: av.layernorm_fwd(xt, gam, bet, yt, mu, rs, 1e-5, stream), args.steps, 5, stream)
+            ms_lb = timed(lambda: av.layernorm_bwd(xt, gam, mu, rs, dyt, dxt, dgam, dbet, lws, stream), args.steps, 5, stream)
+            bf, bb = 4.0 * M * D + 8.0 * M, 6.0 * M * D + 8.0 * M
+            out["layernorm"] = {
+                "shape": [M, D], "fwd_ms": ms_lf, "bwd_ms": ms_lb,
+                "fwd": {"bound": "hbm", "achieved": bf / (ms_lf * 1e-3) / 1e9, "peak": 8000.0, "unit": "GB/s",
+                        "frac": bf / (ms_lf * 1e-3) / 8e12},
+                "bwd": {"bound": "hbm", "achieved": bb / (ms_lb * 1e-3) / 1e9, "peak": 8000.0, "unit": "GB/s",
+                        "frac": bb / (ms_lb * 1e-3) / 8e12},
+                "saved_for_backward_bytes_per_token": 2 * D + 8,
+                "note": "avion_layernorm_fwd / _bwd on the workload's tokens; not part of `value`"}
     if not args.no_cpu_baseline and not f16:
         log(f"[bench] timing the CPU oracle on {args.cpu_clips} clips ...")
         out["cpu_baseline"] = cpu_baseline(w, x, min(args.cpu_clips, w.B))

@@ -207,6 +207,35 @@ int avion_attn_bwd_ex(const void *q, const void *k, const void *v, const void *o
                       void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Layer normalisation over the channel axis, forward and backward: the per-token normalisation in
+ * front of the attention and of the MLP of every encoder layer (Sec. 3, "Video Transformer"), and
+ * one of the three entries of the paper's memory profile (Sec. 4.1).  Per token row x in R^D:
+ *     mu = mean(x), var = mean((x - mu)^2), rstd = 1/sqrt(var + eps),
+ *     y = (x - mu) * rstd * gamma + beta
+ *     dbeta = sum_rows dy;  dgamma = sum_rows dy * xhat;  g = dy * gamma;
+ *     dx = rstd * (g - mean(g) - xhat * mean(g * xhat)),      xhat = (x - mu) * rstd
+ *   x, y, dy, dx   : bf16 (fp16 with AVION_FLAG_F16, the only flag accepted) [M, D] contiguous, device
+ *   gamma, beta, dgamma, dbeta : fp32 [D], device;  mean, rstd : fp32 [M], device
+ *   M >= 1 rows (tokens of all clips); D a multiple of 8, at most 2048; eps finite and >= 0
+ *   workspace (backward): 256-byte aligned, avion_layernorm_bwd_workspace_bytes(M, D) bytes (the
+ *   workgroups' partial sums of dgamma and dbeta: at most 1024 * 2 * D floats, independent of M)
+ * What the backward needs from the forward is x and two floats per row -- the O(N D) activation
+ * memory the paper's profile lists for this layer.  Pointers 16-byte aligned; same stream, error
+ * and ownership rules as every entry point above.  Statistics and sums in fp32, outputs rounded
+ * once; no atomics, results are bit-reproducible.
+ */
+int avion_layernorm_fwd(const void *x, const float *gamma, const float *beta, void *y,
+                        float *mean, float *rstd, long long M, int D, float eps,
+                        unsigned flags, void *stream);
+
+size_t avion_layernorm_bwd_workspace_bytes(long long M, int D);
+
+int avion_layernorm_bwd(const void *x, const float *gamma, const float *mean, const float *rstd,
+                        const void *dy, void *dx, float *dgamma, float *dbeta,
+                        long long M, int D, unsigned flags,
+                        void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Allocation-free backward, for callers that cannot provide device scratch of their own: code
  * under HIP graph capture, tight serving or training loops, harnesses that forbid hipMalloc.
  * Same operation, arguments, rules and bits as avion_attn_bwd (bf16, not causal), without the

@@ -69,6 +69,13 @@ def load_library() -> ctypes.CDLL:
         lib.avion_attn_fwd_ex.argtypes = [p, p, p, p, p, i, i, i, i, f, u, p]
         lib.avion_attn_bwd_ex.restype = i
         lib.avion_attn_bwd_ex.argtypes = [p, p, p, p, p, p, p, p, p, i, i, i, i, f, u, p, sz, p]
+        ll = ctypes.c_longlong
+        lib.avion_layernorm_fwd.restype = i
+        lib.avion_layernorm_fwd.argtypes = [p, p, p, p, p, p, ll, i, f, u, p]
+        lib.avion_layernorm_bwd_workspace_bytes.restype = sz
+        lib.avion_layernorm_bwd_workspace_bytes.argtypes = [ll, i]
+        lib.avion_layernorm_bwd.restype = i
+        lib.avion_layernorm_bwd.argtypes = [p, p, p, p, p, p, p, p, ll, i, u, p, sz, p]
         lib.avion_attn_bwd_noalloc.restype = i
         lib.avion_attn_bwd_noalloc.argtypes = [p, p, p, p, p, p, p, p, p, i, i, i, i, f, p]
         _lib = lib
@@ -293,3 +300,37 @@ def attn_bwd_ex(q, k, v, o, lse, dO, dq, dk, dv, scale: float, workspace, causal
     _check(load_library().avion_attn_bwd_ex(_ptr(q), opt(k), opt(v), _ptr(o), _ptr(lse), _ptr(dO), _ptr(dq), opt(dk),
                                             opt(dv), B, H, N, d, float(scale), _flags(dt, causal, packed),
                                             _ptr(workspace), workspace.numel(), _stream_handle(stream)))
+
+
+def layernorm_bwd_workspace_bytes(M: int, D: int) -> int:
+    return int(load_library().avion_layernorm_bwd_workspace_bytes(M, D))
+
+
+def layernorm_fwd(x, gamma, beta, y, mean, rstd, eps: float, stream=None) -> None:
+    """avion_layernorm_fwd: x, y bf16 or fp16 [M, D]; gamma, beta fp32 [D]; mean, rstd fp32 [M] (saved for the backward)."""
+    import torch
+    M, D = x.shape
+    _require(x, "x", x.dtype, (M, D))
+    _require(y, "y", x.dtype, (M, D))
+    for t, n in ((gamma, "gamma"), (beta, "beta")):
+        _require(t, n, torch.float32, (D,))
+    for t, n in ((mean, "mean"), (rstd, "rstd")):
+        _require(t, n, torch.float32, (M,))
+    _check(load_library().avion_layernorm_fwd(_ptr(x), _ptr(gamma), _ptr(beta), _ptr(y), _ptr(mean), _ptr(rstd), M, D,
+                                              float(eps), _flags(x.dtype, False, False), _stream_handle(stream)))
+
+
+def layernorm_bwd(x, gamma, mean, rstd, dy, dx, dgamma, dbeta, workspace, stream=None) -> None:
+    """avion_layernorm_bwd: dx [M, D] in the format of x; dgamma, dbeta fp32 [D]."""
+    import torch
+    M, D = x.shape
+    for t, n in ((x, "x"), (dy, "dy"), (dx, "dx")):
+        _require(t, n, x.dtype, (M, D))
+    for t, n in ((gamma, "gamma"), (dgamma, "dgamma"), (dbeta, "dbeta")):
+        _require(t, n, torch.float32, (D,))
+    for t, n in ((mean, "mean"), (rstd, "rstd")):
+        _require(t, n, torch.float32, (M,))
+    _require(workspace, "workspace", torch.uint8)
+    _check(load_library().avion_layernorm_bwd(_ptr(x), _ptr(gamma), _ptr(mean), _ptr(rstd), _ptr(dy), _ptr(dx), _ptr(dgamma),
+                                              _ptr(dbeta), M, D, _flags(x.dtype, False, False), _ptr(workspace),
+                                              workspace.numel(), _stream_handle(stream)))

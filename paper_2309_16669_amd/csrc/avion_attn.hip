@@ -14,6 +14,7 @@
 
 #include "avion_bwd.h"
 #include "avion_fwd.h"
+#include "avion_ln.h"
 #include "avion_small.h"
 
 // Built-in scratch of avion_attn_bwd_noalloc: the per-query scalars that the backward's two passes
@@ -381,6 +382,34 @@ int bwd_impl(const void* q, const void* k, const void* v, const void* o, const f
     return dkdv_impl(q, k, v, lse, dO, dk, dv, B, H, N, d, packed, var, scale, workspace, workspace_bytes, stream);
 }
 
+// ------------------------------------------------------------------------------ layer normalisation
+int ln_check(long long M, int D, unsigned flags)
+{
+    if (M < 1 || D < 1) return AVION_EINVAL;
+    if (flags & ~AVION_FLAG_F16) return AVION_EINVAL;
+    if (D % 8 != 0 || D > 64 * 8 * kLnMaxChunks) return AVION_EUNSUPPORTED;
+    if (M > (1LL << 40)) return AVION_EUNSUPPORTED;
+    return AVION_OK;
+}
+unsigned ln_grid(long long M)
+{
+    const long long wgs = (M + kLnWaves - 1) / kLnWaves;
+    return (unsigned)(wgs < kLnMaxGrid ? wgs : kLnMaxGrid);
+}
+// calls f(chunks per lane, element format) with both as compile-time tags
+template <typename F>
+int ln_dispatch(int D, bool f16, F f)
+{
+    const int per_lane = (D / 8 + 63) / 64;
+    auto by_fmt = [&](auto nch) {
+        if (f16) return f(nch, TypeTag<F16>{});
+        return f(nch, TypeTag<Bf16>{});
+    };
+    if (per_lane <= 1) return by_fmt(std::integral_constant<int, 1>{});
+    if (per_lane <= 2) return by_fmt(std::integral_constant<int, 2>{});
+    return by_fmt(std::integral_constant<int, 4>{});
+}
+
 constexpr unsigned kAllFlags = AVION_FLAG_F16 | AVION_FLAG_CAUSAL | AVION_FLAG_QKVPACKED;
 
 // q, k, v planes of a packed [B, N, 3, H, d] tensor
@@ -540,6 +569,63 @@ int avion_attn_bwd_ex(const void* q, const void* k, const void* v, const void* o
                         const_cast<char*>(out.v), B, H, N, d, 3, var, scale, workspace, workspace_bytes, stream);
     }
     return bwd_impl(q, k, v, o, lse, dO, dq, dk, dv, B, H, N, d, 1, var, scale, workspace, workspace_bytes, stream);
+}
+
+int avion_layernorm_fwd(const void* x, const float* gamma, const float* beta, void* y, float* mean, float* rstd,
+                        long long M, int D, float eps, unsigned flags, void* stream)
+{
+    if (!x || !gamma || !beta || !y || !mean || !rstd) return AVION_EINVAL;
+    if (!(eps >= 0.f) || !std::isfinite(eps)) return AVION_EINVAL;
+    const int rc = ln_check(M, D, flags);
+    if (rc != AVION_OK) return rc;
+    const void* ptrs[] = {x, gamma, beta, y, mean, rstd};
+    for (const void* p : ptrs)
+        if (!aligned16(p)) return AVION_EUNSUPPORTED;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    return ln_dispatch(D, (flags & AVION_FLAG_F16) != 0, [&](auto nch, auto fmt) {
+        begin_launch();
+        hipLaunchKernelGGL((avion_ln_fwd_kernel<decltype(nch)::value, typename decltype(fmt)::type>), dim3(ln_grid(M)),
+                           dim3(kLnWaves * 64), 0, st, static_cast<const raw16*>(x), gamma, beta, static_cast<raw16*>(y), mean,
+                           rstd, (long)M, D, eps);
+        return end_launch("launch avion_ln_fwd_kernel");
+    });
+}
+
+size_t avion_layernorm_bwd_workspace_bytes(long long M, int D)
+{
+    if (ln_check(M, D, 0) != AVION_OK) return 0;
+    const size_t bytes = (size_t)ln_grid(M) * 2 * D * sizeof(float);
+    return (bytes + 255) & ~(size_t)255;
+}
+
+int avion_layernorm_bwd(const void* x, const float* gamma, const float* mean, const float* rstd, const void* dy, void* dx,
+                        float* dgamma, float* dbeta, long long M, int D, unsigned flags, void* workspace,
+                        size_t workspace_bytes, void* stream)
+{
+    if (!x || !gamma || !mean || !rstd || !dy || !dx || !dgamma || !dbeta) return AVION_EINVAL;
+    const int rc = ln_check(M, D, flags);
+    if (rc != AVION_OK) return rc;
+    const void* ptrs[] = {x, gamma, mean, rstd, dy, dx, dgamma, dbeta};
+    for (const void* p : ptrs)
+        if (!aligned16(p)) return AVION_EUNSUPPORTED;
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0 ||
+        workspace_bytes < avion_layernorm_bwd_workspace_bytes(M, D))
+        return AVION_EWORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    float* part = static_cast<float*>(workspace);
+    const unsigned grid = ln_grid(M);
+    const int r1 = ln_dispatch(D, (flags & AVION_FLAG_F16) != 0, [&](auto nch, auto fmt) {
+        begin_launch();
+        hipLaunchKernelGGL((avion_ln_bwd_kernel<decltype(nch)::value, typename decltype(fmt)::type>), dim3(grid),
+                           dim3(kLnWaves * 64), (kLnWaves - 1) * 2 * D * sizeof(float), st, static_cast<const raw16*>(x), gamma,
+                           mean, rstd, static_cast<const raw16*>(dy), static_cast<raw16*>(dx), part, (long)M, D);
+        return end_launch("launch avion_ln_bwd_kernel");
+    });
+    if (r1 != AVION_OK) return r1;
+    begin_launch();
+    hipLaunchKernelGGL(avion_ln_param_reduce_kernel, dim3((2 * D + kLnReduceCols - 1) / kLnReduceCols),
+                       dim3(kLnReduceCols * kLnReduceGroups), 0, st, part, dgamma, dbeta, (int)grid, D);
+    return end_launch("launch avion_ln_param_reduce_kernel");
 }
 
 }  // extern "C"

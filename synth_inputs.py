@@ -61,24 +61,37 @@ def f16_bits_to_f64(b: np.ndarray) -> np.ndarray:
     return np.ascontiguousarray(b, dtype=np.uint16).view(np.float16).astype(np.float64)
 
 
+def _normal_f64(seed: int, stream: int, start: int, n: int) -> np.ndarray:
+    """Elements start..start+n-1 of the N(0,1) stream (seed, stream), in fp64."""
+    with np.errstate(over="ignore"):
+        key = _mix64(np.uint64(seed & 0xFFFFFFFFFFFFFFFF) * _GOLD + np.uint64(stream + 1) * _M2)
+        idx = np.arange(start, start + n, dtype=np.uint64)
+        a = _mix64(key + (idx * np.uint64(2) + np.uint64(1)) * _GOLD)
+        b = _mix64(key + (idx * np.uint64(2) + np.uint64(2)) * _GOLD)
+    # u1 in (0,1], u2 in [0,1): 53-bit mantissas
+    u1 = ((a >> np.uint64(11)).astype(np.float64) + 1.0) * (1.0 / 9007199254740992.0)
+    u2 = (b >> np.uint64(11)).astype(np.float64) * (1.0 / 9007199254740992.0)
+    return np.sqrt(-2.0 * np.log(u1)) * np.cos((2.0 * math.pi) * u2)
+
+
 def normal_bf16_bits(seed: int, stream: int, count: int, offset: int = 0, chunk: int = 1 << 22,
                      to_bits=None) -> np.ndarray:
     """`count` iid N(0,1) draws, elements offset..offset+count-1 of (seed, stream), as bf16 bits
     (or, with to_bits=f32_to_f16_bits, the same draws rounded to fp16)."""
     to_bits = to_bits or f32_to_bf16_bits
     out = np.empty(count, dtype=np.uint16)
-    with np.errstate(over="ignore"):
-        key = _mix64(np.uint64(seed & 0xFFFFFFFFFFFFFFFF) * _GOLD + np.uint64(stream + 1) * _M2)
-        for start in range(0, count, chunk):
-            n = min(chunk, count - start)
-            idx = np.arange(offset + start, offset + start + n, dtype=np.uint64)
-            a = _mix64(key + (idx * np.uint64(2) + np.uint64(1)) * _GOLD)
-            b = _mix64(key + (idx * np.uint64(2) + np.uint64(2)) * _GOLD)
-            # u1 in (0,1], u2 in [0,1): 53-bit mantissas
-            u1 = ((a >> np.uint64(11)).astype(np.float64) + 1.0) * (1.0 / 9007199254740992.0)
-            u2 = (b >> np.uint64(11)).astype(np.float64) * (1.0 / 9007199254740992.0)
-            z = np.sqrt(-2.0 * np.log(u1)) * np.cos((2.0 * math.pi) * u2)
-            out[start:start + n] = to_bits(z.astype(np.float32))
+    for start in range(0, count, chunk):
+        n = min(chunk, count - start)
+        out[start:start + n] = to_bits(_normal_f64(seed, stream, offset + start, n).astype(np.float32))
+    return out
+
+
+def normal_f32(seed: int, stream: int, count: int, offset: int = 0, chunk: int = 1 << 22) -> np.ndarray:
+    """The same draws, rounded to fp32 only (for fp32 parameters such as a normalisation's gain)."""
+    out = np.empty(count, dtype=np.float32)
+    for start in range(0, count, chunk):
+        n = min(chunk, count - start)
+        out[start:start + n] = _normal_f64(seed, stream, offset + start, n).astype(np.float32)
     return out
 
 
@@ -153,3 +166,16 @@ def small_workload(B, H, N, d, seed, scale=None, k_mul=1.0, name=None) -> Worklo
     if scale is None:
         scale = 1.0 / math.sqrt(d)
     return Workload(name or f"small_B{B}_H{H}_N{N}_d{d}", B, H, N, d, scale, seed, k_mul)
+
+
+
+def layernorm_inputs(M: int, D: int, seed: int, fmt: str = "bf16") -> dict:
+    """Seeded inputs of a layer normalisation over [M, D] tokens: x and dy ~ N(0,1) as bit patterns of
+    `fmt`, gain 1 + 0.1 N(0,1) and bias 0.1 N(0,1) in fp32 (stand-ins for trained parameters)."""
+    to_bits = f32_to_f16_bits if fmt == "f16" else f32_to_bf16_bits
+    return {
+        "x": normal_bf16_bits(seed, 10, M * D, to_bits=to_bits).reshape(M, D),
+        "dy": normal_bf16_bits(seed, 11, M * D, to_bits=to_bits).reshape(M, D),
+        "gamma": (np.float32(1.0) + np.float32(0.1) * normal_f32(seed, 12, D)).astype(np.float32),
+        "beta": (np.float32(0.1) * normal_f32(seed, 13, D)).astype(np.float32),
+    }
