@@ -34,12 +34,21 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published figure
 # HBM bytes per launch (FETCH_SIZE + WRITE_SIZE from rocprofv3 --pmc, scaled by a copy kernel of
 # known size); filled in from the summaries under profiles/ -- None until measured.
 MEASURED_HBM_BYTES_PER_LAUNCH = {
-    # (workload, dtype, kernel) -> (bytes per launch, summary under profiles/ that holds the counters).
-    # FETCH_SIZE x 2.0 (copy-kernel factor) + WRITE_SIZE x 1.0.  Measured offline on the default
-    # configuration (separate q/k/v tensors, recipe operands); any other run prints null with the reason.
-    ("vitb_batch", "bf16", "avion_fwd_kernel"): (312.0e6, "profiles/hbm_traffic_vitb_batch.txt"),
-    ("vitb_batch", "bf16", "avion_dq_kernel"): (473.1e6, "profiles/hbm_traffic_vitb_batch.txt"),
-    ("vitb_batch", "bf16", "avion_dkdv_kernel"): (471.3e6, "profiles/hbm_traffic_vitb_batch.txt"),
+    # (workload, dtype, kernel) -> (bytes per launch, summary under profiles/ that holds the counters):
+    # (2.0 x FETCH_SIZE + 1.0 x WRITE_SIZE) KiB, the factors being what the same counters read for a plain copy of
+    # known size.  Measured offline on separate q/k/v tensors with N(0,1) operands; any other run prints null.
+    ("vitb_batch", "bf16", "avion_fwd_kernel"): (3.1236e+08, "profiles/vitb_batch_bf16.txt"),
+    ("vitb_batch", "bf16", "avion_dq_kernel"): (4.7273e+08, "profiles/vitb_batch_bf16.txt"),
+    ("vitb_batch", "bf16", "avion_dkdv_kernel"): (5.1175e+08, "profiles/vitb_batch_bf16.txt"),
+    ("vitb_batch", "f16", "avion_fwd_kernel"): (3.1248e+08, "profiles/vitb_batch_f16.txt"),
+    ("vitb_batch", "f16", "avion_dq_kernel"): (4.7330e+08, "profiles/vitb_batch_f16.txt"),
+    ("vitb_batch", "f16", "avion_dkdv_kernel"): (5.1204e+08, "profiles/vitb_batch_f16.txt"),
+    ("vith_d80", "bf16", "avion_fwd_kernel"): (1.3885e+08, "profiles/vith_d80.txt"),
+    ("vith_d80", "bf16", "avion_dq_kernel"): (2.1919e+08, "profiles/vith_d80.txt"),
+    ("vith_d80", "bf16", "avion_dkdv_kernel"): (2.2141e+08, "profiles/vith_d80.txt"),
+    ("vitb_long", "bf16", "avion_fwd_kernel"): (1.5898e+08, "profiles/vitb_long.txt"),
+    ("vitb_long", "bf16", "avion_dq_kernel"): (2.4761e+08, "profiles/vitb_long.txt"),
+    ("vitb_long", "bf16", "avion_dkdv_kernel"): (2.6611e+08, "profiles/vitb_long.txt"),
 }
 PREWARM_SECONDS = 0.3
 
@@ -113,6 +122,10 @@ def main():
                     help="skip the extra timing of the step of a layer trained with gradient checkpointing "
                          "(Sec. 4.1 of the paper: the forward runs a second time before the backward), which is "
                          "reported beside the metric and does not change it")
+    ap.add_argument("--device-rng", action="store_true",
+                    help="draw the N(0,1) inputs with the device's generator instead of the seeded recipe (same "
+                         "distribution, seconds instead of minutes for the large small-sequence workloads; for "
+                         "profiling runs -- the CPU baseline is skipped)")
     ap.add_argument("--no-layernorm", action="store_true", help="skip the layer-normalisation block of the line")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain device copy of Q (known size) so that HBM counters of a "
@@ -136,15 +149,23 @@ def main():
     w = si.WORKLOADS[args.workload]
     log(f"[bench] generating {w.name} {w.shape} ...")
     f16 = args.dtype == "f16"
-    x = si.make_inputs(w, fmt=args.dtype)
     dev = torch.device("cuda:0")
+    x = None if args.device_rng else si.make_inputs(w, fmt=args.dtype)
 
     def up(bits):
         import numpy as np
         return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(dev).view(
             torch.float16 if f16 else torch.bfloat16)
 
-    q, k, v, dO = (up(x[n]) for n in ("q", "k", "v", "dO"))
+    if args.device_rng:
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(w.seed)
+        q, k, v, dO = (torch.randn(w.shape, device=dev, generator=gen, dtype=torch.float32).to(
+            torch.float16 if f16 else torch.bfloat16) for _ in range(4))
+        if w.k_mul != 1.0:
+            k = k * w.k_mul
+    else:
+        q, k, v, dO = (up(x[n]) for n in ("q", "k", "v", "dO"))
     if args.operands != "recipe":
         for t in (q, k, v, dO):
             t.fill_(0.0 if args.operands == "zeros" else 1.0)
@@ -240,6 +261,10 @@ def main():
     dom_name = max(dom, key=lambda n: dom[n][0])
     dom_ms, dom_flops = dom[dom_name]
     achieved = tf(dom_flops, dom_ms)
+    # short sequences are bound by memory bandwidth (N/2 flops per byte in the forward, below the chip's
+    # ~310): there the whole backward / forward launch is rated by its algorithmic bytes against HBM
+    hbm_bound = w.N <= 256
+    tensor_bytes = 2.0 * w.B * w.N * w.H * w.d
 
     out = {
         "metric": "attention fwd+bwd TFLOP/s (N=1568,d=64) and % of MI355X bf16 MFMA peak",
@@ -250,7 +275,7 @@ def main():
         "timing": "HIP events on the launch stream around exactly K steps, after an untimed pre-warm of "
                   f"{PREWARM_SECONDS} s and W warm-up steps",
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": args.dtype, "data": "synthetic" if args.operands == "recipe" else f"constant operands ({args.operands}), diagnostic only",
+        "dtype": args.dtype, "data": ("synthetic" if not args.device_rng else "synthetic (device generator)") if args.operands == "recipe" else f"constant operands ({args.operands}), diagnostic only",
         "config": {"workload": f"{w.name}: B={w.B} H={w.H} N={w.N} d={w.d} {'causal' if args.causal else 'non-causal'}, scale={w.scale:g}, "
                                f"Q/K/V/dO ~ N(0,1) {args.dtype}, fwd+bwd" + (", packed [B,N,3,H,d] QKV" if packed else "")
                                + (", CAUSAL variant (diagnostic)" if args.causal else "")},
@@ -265,6 +290,15 @@ def main():
                      "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
                      "algorithmic_flops_per_launch": dom_flops, "avg_launch_ms": dom_ms},
     }
+    if hbm_bound:
+        bwd_dom = ms_bwd >= ms_fwd
+        nbytes = (8.0 if bwd_dom else 4.0) * tensor_bytes + 4.0 * w.B * w.H * w.N
+        rate = nbytes / ((ms_bwd if bwd_dom else ms_fwd) * 1e-3) / 1e9
+        out["roofline"] = {"bound": "hbm", "kernel": "backward launch(es)" if bwd_dom else "forward launch",
+                           "achieved": rate, "peak": 8000.0, "unit": "GB/s", "frac": rate / 8000.0, "traffic": None,
+                           "algorithmic_bytes_per_launch": nbytes, "avg_launch_ms": ms_bwd if bwd_dom else ms_fwd,
+                           "other": {"fwd_GBps": (4.0 * tensor_bytes) / (ms_fwd * 1e-3) / 1e9,
+                                     "bwd_GBps": (8.0 * tensor_bytes) / (ms_bwd * 1e-3) / 1e9}}
     entry = MEASURED_HBM_BYTES_PER_LAUNCH.get((args.workload, args.dtype, dom_name))
     if entry is not None and not packed and not args.causal and args.operands == "recipe":
         out["roofline"]["traffic"] = entry[0]
@@ -305,7 +339,7 @@ def main():
                         "frac": bb / (ms_lb * 1e-3) / 8e12},
                 "saved_for_backward_bytes_per_token": 2 * D + 8,
                 "note": "avion_layernorm_fwd / _bwd on the workload's tokens; not part of `value`"}
-    if not args.no_cpu_baseline and not f16:
+    if not args.no_cpu_baseline and not f16 and not args.device_rng:
         log(f"[bench] timing the CPU oracle on {args.cpu_clips} clips ...")
         out["cpu_baseline"] = cpu_baseline(w, x, min(args.cpu_clips, w.B))
     print(json.dumps(out), flush=True)

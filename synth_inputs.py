@@ -136,6 +136,18 @@ WORKLOADS = {
     ]
 }
 
+# Shapes of the small-sequence regime (not among the named benchmark configurations): the text encoder of
+# the video-language model (at most 77 tokens, causal) for 2048 captions, and the two attentions of a
+# divided space/time model (the comparison architecture of Sec. 4.1) on 32 clips of 8 frames.
+WORKLOADS.update({
+    w.name: w
+    for w in [
+        Workload("text_77", 2048, 8, 77, 64, 0.125, 230916701, note="text-encoder layer, 2048 captions of 77 tokens (use the causal entry points)"),
+        Workload("temporal_16", 32 * 196, 12, 16, 64, 0.125, 230916702, note="temporal attention: one problem of T = 16 frames per spatial position"),
+        Workload("spatial_196", 32 * 8, 12, 196, 64, 0.125, 230916703, note="spatial attention: one problem of 14 x 14 tokens per frame"),
+    ]
+})
+
 STREAMS = {"q": 0, "k": 1, "v": 2, "dO": 3}
 
 
