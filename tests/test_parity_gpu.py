@@ -468,6 +468,23 @@ def test_whole_backward_equals_its_two_phases(B, H, N, d):
         assert torch.equal(whole[n].view(torch.int16), t.view(torch.int16)), n
 
 
+@pytest.mark.parametrize("B,H,N,d", [(3, 5, 100, 64), (2, 2, 128, 64), (2, 3, 77, 80), (4, 2, 20, 64)])
+def test_the_two_phases_stay_callable_on_short_sequences(B, H, N, d):
+    # avion_attn_bwd_dq + avion_attn_bwd_dkdv on shapes that avion_attn_bwd itself runs in one launch
+    import torch
+    import paper_2309_16669_amd as av
+    w = si.small_workload(B, H, N, d, seed=5250 + N)
+    x = si.make_inputs(w)
+    whole = gh.run_hip(w, x)
+    q, k, v, dO = (gh.to_gpu_bf16(x[n]) for n in ("q", "k", "v", "dO"))
+    dq, dk, dv = (torch.full_like(q, float("nan")) for _ in range(3))
+    ws = torch.empty(av.attn_bwd_workspace_bytes(w.B, w.H, w.N, w.d), dtype=torch.uint8, device="cuda")
+    av.attn_bwd_dq(q, k, v, whole["o"], whole["lse"], dO, dq, w.scale, ws)
+    av.attn_bwd_dkdv(q, k, v, whole["lse"], dO, dk, dv, w.scale, ws)
+    torch.cuda.synchronize()
+    gh.check_against_oracle(w, x, dict(whole, dq=dq, dk=dk, dv=dv))
+
+
 def test_calls_can_be_captured_in_a_graph_and_replayed():
     # the entry points only enqueue kernels on the caller's stream (no allocation, no memset, no
     # synchronisation), so a forward + backward can be recorded into a HIP graph; every replay, with
