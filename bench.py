@@ -126,7 +126,7 @@ def main():
                     help="draw the N(0,1) inputs with the device's generator instead of the seeded recipe (same "
                          "distribution, seconds instead of minutes for the large small-sequence workloads; for "
                          "profiling runs -- the CPU baseline is skipped)")
-    ap.add_argument("--no-layernorm", action="store_true", help="skip the layer-normalisation block of the line")
+    ap.add_argument("--no-layernorm", action="store_true", help="skip the layer-normalisation and bias + GELU blocks of the line")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain device copy of Q (known size) so that HBM counters of a "
                          "rocprofv3 --pmc run can be scaled")
@@ -339,6 +339,28 @@ def main():
                         "frac": bb / (ms_lb * 1e-3) / 8e12},
                 "saved_for_backward_bytes_per_token": 2 * D + 8,
                 "note": "avion_layernorm_fwd / _bwd on the workload's tokens; not part of `value`"}
+            del xt, dyt, yt, dxt
+        # the bias + GELU step of the layer's MLP on the same tokens ([B*N, 4*H*d]); algorithmic bytes:
+        # forward reads x and writes y, backward reads x and dy and writes dx
+        F = 4 * D
+        if F % 8 == 0 and F <= 65536:
+            xt = (1.5 * torch.randn((M, F), device=dev)).to(q.dtype)
+            dyt = torch.randn((M, F), device=dev).to(q.dtype)
+            bia, dbia = 0.1 * torch.randn(F, device=dev), torch.empty(F, device=dev)
+            yt, dxt = torch.empty_like(xt), torch.empty_like(xt)
+            gws = torch.empty(av.bias_gelu_bwd_workspace_bytes(M, F), dtype=torch.uint8, device=dev)
+            ms_gf = timed(lambda: av.bias_gelu_fwd(xt, bia, yt, stream), args.steps, 5, stream)
+            ms_gb = timed(lambda: av.bias_gelu_bwd(xt, bia, dyt, dxt, dbia, gws, stream), args.steps, 5, stream)
+            gf, gb = 4.0 * M * F, 6.0 * M * F
+            out["mlp_bias_gelu"] = {
+                "shape": [M, F], "fwd_ms": ms_gf, "bwd_ms": ms_gb,
+                "fwd": {"bound": "hbm", "achieved": gf / (ms_gf * 1e-3) / 1e9, "peak": 8000.0, "unit": "GB/s",
+                        "frac": gf / (ms_gf * 1e-3) / 8e12},
+                "bwd": {"bound": "hbm", "achieved": gb / (ms_gb * 1e-3) / 1e9, "peak": 8000.0, "unit": "GB/s",
+                        "frac": gb / (ms_gb * 1e-3) / 8e12},
+                "saved_for_backward_bytes_per_token": 2 * F,
+                "note": "avion_bias_gelu_fwd / _bwd on the workload's tokens at the MLP width; not part of `value`"}
+            del xt, dyt, yt, dxt
     if not args.no_cpu_baseline and not f16 and not args.device_rng:
         log(f"[bench] timing the CPU oracle on {args.cpu_clips} clips ...")
         out["cpu_baseline"] = cpu_baseline(w, x, min(args.cpu_clips, w.B))

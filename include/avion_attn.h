@@ -236,6 +236,37 @@ int avion_layernorm_bwd(const void *x, const float *gamma, const float *mean, co
                         void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Bias + GELU, forward and backward: the elementwise step between the two matrix products of the
+ * encoder's 2-layer MLP (Sec. 3, "Video Transformer"), the third entry of the paper's memory
+ * profile (Sec. 4.1, figure "memory footprint").  The paper names no activation; this is the
+ * exact (erf) GELU of the plain ViT.  Per element, with h = x + bias_c:
+ *     y  = h * Phi(h)                       Phi = standard normal distribution function
+ *     dx = dy * (Phi(h) + h * phi(h))       phi = its density
+ *     dbias_c = sum over rows of dx_c       (from the fp32 dx, before it is rounded)
+ *   x, dy    : in,  bf16 (fp16 with AVION_FLAG_F16, the only flag accepted) [M, F] contiguous;
+ *              x is the first matrix product's output WITHOUT the bias
+ *   bias     : in,  fp32 [F];   dbias : out, fp32 [F], fully overwritten
+ *   y, dx    : out, same format and shape as x, fully overwritten; may not alias the inputs
+ *   M >= 1 rows (tokens); F % 8 == 0, F <= 65536 (else AVION_EUNSUPPORTED)
+ *   workspace (backward): 256-byte aligned, avion_bias_gelu_bwd_workspace_bytes(M, F) bytes
+ *   (partial sums of dbias: at most 4096 * 1024 floats, independent of M)
+ * The backward rebuilds Phi and phi from x and bias, so the activation's output need not be kept
+ * for it: with it the MLP keeps F * 2 bytes per token for this step instead of 2 * F * 2 (the
+ * second matrix product's own input is rebuilt by one more avion_bias_gelu_fwd when its weight
+ * gradient is formed).  erf by a five-term rational approximation with absolute error < 1.5e-7,
+ * arithmetic in fp32, outputs rounded once; no atomics, results are bit-reproducible.
+ * Pointers 16-byte aligned; same stream, error and ownership rules as every entry point above.
+ */
+int avion_bias_gelu_fwd(const void *x, const float *bias, void *y, long long M, int F,
+                        unsigned flags, void *stream);
+
+size_t avion_bias_gelu_bwd_workspace_bytes(long long M, int F);
+
+int avion_bias_gelu_bwd(const void *x, const float *bias, const void *dy, void *dx, float *dbias,
+                        long long M, int F, unsigned flags,
+                        void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Allocation-free backward, for callers that cannot provide device scratch of their own: code
  * under HIP graph capture, tight serving or training loops, harnesses that forbid hipMalloc.
  * Same operation, arguments, rules and bits as avion_attn_bwd (bf16, not causal), without the

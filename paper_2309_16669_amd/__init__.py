@@ -76,6 +76,12 @@ def load_library() -> ctypes.CDLL:
         lib.avion_layernorm_bwd_workspace_bytes.argtypes = [ll, i]
         lib.avion_layernorm_bwd.restype = i
         lib.avion_layernorm_bwd.argtypes = [p, p, p, p, p, p, p, p, ll, i, u, p, sz, p]
+        lib.avion_bias_gelu_fwd.restype = i
+        lib.avion_bias_gelu_fwd.argtypes = [p, p, p, ll, i, u, p]
+        lib.avion_bias_gelu_bwd_workspace_bytes.restype = sz
+        lib.avion_bias_gelu_bwd_workspace_bytes.argtypes = [ll, i]
+        lib.avion_bias_gelu_bwd.restype = i
+        lib.avion_bias_gelu_bwd.argtypes = [p, p, p, p, p, ll, i, u, p, sz, p]
         lib.avion_attn_bwd_noalloc.restype = i
         lib.avion_attn_bwd_noalloc.argtypes = [p, p, p, p, p, p, p, p, p, i, i, i, i, f, p]
         _lib = lib
@@ -334,3 +340,32 @@ def layernorm_bwd(x, gamma, mean, rstd, dy, dx, dgamma, dbeta, workspace, stream
     _check(load_library().avion_layernorm_bwd(_ptr(x), _ptr(gamma), _ptr(mean), _ptr(rstd), _ptr(dy), _ptr(dx), _ptr(dgamma),
                                               _ptr(dbeta), M, D, _flags(x.dtype, False, False), _ptr(workspace),
                                               workspace.numel(), _stream_handle(stream)))
+
+
+def bias_gelu_bwd_workspace_bytes(M: int, F: int) -> int:
+    return int(load_library().avion_bias_gelu_bwd_workspace_bytes(M, F))
+
+
+def bias_gelu_fwd(x, bias, y, stream=None) -> None:
+    """avion_bias_gelu_fwd: x, y bf16 or fp16 [M, F]; bias fp32 [F]."""
+    import torch
+    M, F = x.shape
+    _require(x, "x", x.dtype, (M, F))
+    _require(y, "y", x.dtype, (M, F))
+    _require(bias, "bias", torch.float32, (F,))
+    _check(load_library().avion_bias_gelu_fwd(_ptr(x), _ptr(bias), _ptr(y), M, F, _flags(x.dtype, False, False),
+                                              _stream_handle(stream)))
+
+
+def bias_gelu_bwd(x, bias, dy, dx, dbias, workspace, stream=None) -> None:
+    """avion_bias_gelu_bwd: dx [M, F] in the format of x; dbias fp32 [F]."""
+    import torch
+    M, F = x.shape
+    for t, n in ((x, "x"), (dy, "dy"), (dx, "dx")):
+        _require(t, n, x.dtype, (M, F))
+    for t, n in ((bias, "bias"), (dbias, "dbias")):
+        _require(t, n, torch.float32, (F,))
+    _require(workspace, "workspace", torch.uint8)
+    _check(load_library().avion_bias_gelu_bwd(_ptr(x), _ptr(bias), _ptr(dy), _ptr(dx), _ptr(dbias), M, F,
+                                              _flags(x.dtype, False, False), _ptr(workspace), workspace.numel(),
+                                              _stream_handle(stream)))

@@ -16,6 +16,7 @@
 #include "avion_fwd.h"
 #include "avion_ln.h"
 #include "avion_small.h"
+#include "avion_gelu.h"
 
 // Built-in scratch of avion_attn_bwd_noalloc: the per-query scalars that the backward's two passes
 // hand to each other live here instead of in a caller's workspace.  One copy per GPU, held until
@@ -410,6 +411,29 @@ int ln_dispatch(int D, bool f16, F f)
     return by_fmt(std::integral_constant<int, 4>{});
 }
 
+// ------------------------------------------------------------------------------------ bias + GELU
+constexpr int kGeluMaxF = 1 << 16;
+int gelu_check(long long M, int F, unsigned flags)
+{
+    if (M < 1 || F < 1) return AVION_EINVAL;
+    if (flags & ~AVION_FLAG_F16) return AVION_EINVAL;
+    if (F % 8 != 0 || F > kGeluMaxF) return AVION_EUNSUPPORTED;
+    if (M > (1LL << 40)) return AVION_EUNSUPPORTED;
+    return AVION_OK;
+}
+// column blocks of 1024 columns, and row groups so that the launch has at most kGeluMaxGrid workgroups
+struct GeluGrid {
+    int ncb, nrg;
+};
+GeluGrid gelu_grid(long long M, int F)
+{
+    GeluGrid g;
+    g.ncb = (F / 8 + kGeluThreads - 1) / kGeluThreads;
+    const long long most = kGeluMaxGrid / g.ncb;
+    g.nrg = (int)(M < most ? M : most);
+    return g;
+}
+
 constexpr unsigned kAllFlags = AVION_FLAG_F16 | AVION_FLAG_CAUSAL | AVION_FLAG_QKVPACKED;
 
 // q, k, v planes of a packed [B, N, 3, H, d] tensor
@@ -429,7 +453,7 @@ struct Planes {
 
 extern "C" {
 
-int avion_version(void) { return 20100; }  // 2.1.0
+int avion_version(void) { return 20200; }  // 2.2.0
 
 const char* avion_strerror(int code)
 {
@@ -625,6 +649,64 @@ int avion_layernorm_bwd(const void* x, const float* gamma, const float* mean, co
     begin_launch();
     hipLaunchKernelGGL(avion_ln_param_reduce_kernel, dim3((2 * D + kLnReduceCols - 1) / kLnReduceCols),
                        dim3(kLnReduceCols * kLnReduceGroups), 0, st, part, dgamma, dbeta, (int)grid, D);
+    return end_launch("launch avion_ln_param_reduce_kernel");
+}
+
+size_t avion_bias_gelu_bwd_workspace_bytes(long long M, int F)
+{
+    if (gelu_check(M, F, 0) != AVION_OK) return 0;
+    const size_t bytes = (size_t)gelu_grid(M, F).nrg * F * sizeof(float);
+    return (bytes + 255) & ~(size_t)255;
+}
+
+int avion_bias_gelu_fwd(const void* x, const float* bias, void* y, long long M, int F, unsigned flags, void* stream)
+{
+    if (!x || !bias || !y) return AVION_EINVAL;
+    const int rc = gelu_check(M, F, flags);
+    if (rc != AVION_OK) return rc;
+    if (!aligned16(x) || !aligned16(y) || !aligned16(bias)) return AVION_EUNSUPPORTED;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const GeluGrid g = gelu_grid(M, F);
+    begin_launch();
+    if (flags & AVION_FLAG_F16)
+        hipLaunchKernelGGL(avion_bias_gelu_fwd_kernel<F16>, dim3((unsigned)(g.ncb * g.nrg)), dim3(kGeluThreads), 0, st,
+                           static_cast<const raw16*>(x), bias, static_cast<raw16*>(y), (long)M, F, g.ncb);
+    else
+        hipLaunchKernelGGL(avion_bias_gelu_fwd_kernel<Bf16>, dim3((unsigned)(g.ncb * g.nrg)), dim3(kGeluThreads), 0, st,
+                           static_cast<const raw16*>(x), bias, static_cast<raw16*>(y), (long)M, F, g.ncb);
+    return end_launch("launch avion_bias_gelu_fwd_kernel");
+}
+
+int avion_bias_gelu_bwd(const void* x, const float* bias, const void* dy, void* dx, float* dbias, long long M, int F,
+                        unsigned flags, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!x || !bias || !dy || !dx || !dbias) return AVION_EINVAL;
+    const int rc = gelu_check(M, F, flags);
+    if (rc != AVION_OK) return rc;
+    const void* ptrs[] = {x, bias, dy, dx, dbias};
+    for (const void* p : ptrs)
+        if (!aligned16(p)) return AVION_EUNSUPPORTED;
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0 ||
+        workspace_bytes < avion_bias_gelu_bwd_workspace_bytes(M, F))
+        return AVION_EWORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    float* part = static_cast<float*>(workspace);
+    const GeluGrid g = gelu_grid(M, F);
+    begin_launch();
+    if (flags & AVION_FLAG_F16)
+        hipLaunchKernelGGL(avion_bias_gelu_bwd_kernel<F16>, dim3((unsigned)(g.ncb * g.nrg)), dim3(kGeluThreads), 0, st,
+                           static_cast<const raw16*>(x), bias, static_cast<const raw16*>(dy), static_cast<raw16*>(dx), part,
+                           (long)M, F, g.ncb);
+    else
+        hipLaunchKernelGGL(avion_bias_gelu_bwd_kernel<Bf16>, dim3((unsigned)(g.ncb * g.nrg)), dim3(kGeluThreads), 0, st,
+                           static_cast<const raw16*>(x), bias, static_cast<const raw16*>(dy), static_cast<raw16*>(dx), part,
+                           (long)M, F, g.ncb);
+    const int r1 = end_launch("launch avion_bias_gelu_bwd_kernel");
+    if (r1 != AVION_OK) return r1;
+    // column sums of the row groups' partials: the reduction kernel splits its 2 * (F / 2) columns into two outputs
+    begin_launch();
+    hipLaunchKernelGGL(avion_ln_param_reduce_kernel, dim3((F + kLnReduceCols - 1) / kLnReduceCols),
+                       dim3(kLnReduceCols * kLnReduceGroups), 0, st, part, dbias, dbias + F / 2, g.nrg, F / 2);
     return end_launch("launch avion_ln_param_reduce_kernel");
 }
 

@@ -191,3 +191,17 @@ def layernorm_inputs(M: int, D: int, seed: int, fmt: str = "bf16") -> dict:
         "gamma": (np.float32(1.0) + np.float32(0.1) * normal_f32(seed, 12, D)).astype(np.float32),
         "beta": (np.float32(0.1) * normal_f32(seed, 13, D)).astype(np.float32),
     }
+
+
+def gelu_inputs(M: int, F: int, seed: int, fmt: str = "bf16") -> dict:
+    """Seeded inputs of a bias + GELU step over [M, F]: x ~ 1.5 N(0,1) (the first MLP layer's output
+    without bias; wide enough to reach both tails of the activation) and dy ~ N(0,1) as bit patterns of
+    `fmt`, bias 0.1 N(0,1) in fp32."""
+    to_bits = f32_to_f16_bits if fmt == "f16" else f32_to_bf16_bits
+    x = (np.float32(1.5) * normal_f32(seed, 20, M * F)).astype(np.float32)
+    return {
+        "x": to_bits(x).reshape(M, F),
+        "dy": normal_bf16_bits(seed, 21, M * F, to_bits=to_bits).reshape(M, F),
+        "bias": (np.float32(0.1) * normal_f32(seed, 22, F)).astype(np.float32),
+    }
+

@@ -1,0 +1,128 @@
+"""GPU parity of the bias + GELU kernels (through the C ABI) against the fp64 oracle (oracle/gelu.py) on
+the same seeded inputs.
+
+Bounds, from the arithmetic (everything in fp32 from exactly widened inputs, erf by a rational
+approximation with absolute error < 1.5e-7, one rounding to the tensor format, whose half spacing is
+at most 2 u |value| with u = 2^-9 for bf16, 2^-12 for fp16):
+  y, dx   every element within 2.02 u |ref| + 1e-6 max(1, max|h|, max|dy|) (its own rounding plus the
+          absolute error of the approximation times |h| or |dy|); relative Frobenius error <= 2.5 u as
+          for the layer normalisation (the rounding alone gives about u)
+  dbias   relative Frobenius error <= 1e-4 (fp32 sums over all rows of the unrounded dx)
+"""
+import ctypes
+
+import numpy as np
+import pytest
+
+import synth_inputs as si
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(M, F, seed, fmt="bf16"):
+    import torch
+    import paper_2309_16669_amd as av
+    dt = torch.float16 if fmt == "f16" else torch.bfloat16
+    inp = si.gelu_inputs(M, F, seed, fmt)
+    up = lambda bits: torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(dt)
+    x, dy, bias = up(inp["x"]), up(inp["dy"]), torch.from_numpy(inp["bias"]).cuda()
+    y, dx = torch.full_like(x, float("nan")), torch.full_like(x, float("nan"))
+    dbias = torch.full((F,), float("nan"), dtype=torch.float32, device="cuda")
+    ws = torch.empty(av.bias_gelu_bwd_workspace_bytes(M, F), dtype=torch.uint8, device="cuda")
+    av.bias_gelu_fwd(x, bias, y)
+    av.bias_gelu_bwd(x, bias, dy, dx, dbias, ws)
+    torch.cuda.synchronize()
+    return inp, dict(y=y, dx=dx, dbias=dbias)
+
+
+def _check(M, F, seed, fmt="bf16"):
+    from oracle import gelu
+    inp, out = _run(M, F, seed, fmt)
+    widen = si.f16_bits_to_f64 if fmt == "f16" else si.bf16_bits_to_f64
+    u = 2.0 ** -12 if fmt == "f16" else 2.0 ** -9
+    x, dy = widen(inp["x"]), widen(inp["dy"])
+    ry = gelu.fwd(x, inp["bias"])
+    rdx, rdb = gelu.bwd(x, inp["bias"], dy)
+    floor = 1e-6 * max(1.0, float(np.abs(x).max()), float(np.abs(dy).max()))
+    rep = {}
+    for name, ref in (("y", ry), ("dx", rdx)):
+        got = out[name].double().cpu().numpy()
+        assert np.all(np.isfinite(got)), name
+        err = np.abs(got - ref)
+        assert np.all(err <= 2.02 * u * np.abs(ref) + floor), (name, float((err - 2.02 * u * np.abs(ref)).max()))
+        rel = np.sqrt((err ** 2).sum() / max((ref ** 2).sum(), 1e-300))
+        rep[name] = (float(err.max()), float(rel))
+        assert rel <= 2.5 * u, (name, rel)
+    got = out["dbias"].double().cpu().numpy()
+    rel = np.sqrt(((got - rdb) ** 2).sum() / max((rdb ** 2).sum(), 1e-300))
+    rep["dbias"] = float(rel)
+    assert rel <= 1e-4, rel
+    return rep
+
+
+# fewer columns than one workgroup owns, exactly one and several column blocks with a ragged last one,
+# the MLP widths of ViT-B/L/H (3072, 4096, 5120), row counts around the rows in flight and the grid
+SHAPES = [(1, 8), (3, 40), (5, 1024), (7, 1032), (33, 3072), (130, 200), (1000, 4096), (257, 5120), (4099, 768), (9, 2056)]
+
+
+@pytest.mark.parametrize("M,F", SHAPES)
+@pytest.mark.parametrize("fmt", ["bf16", "f16"])
+def test_shapes_match_the_oracle(M, F, fmt):
+    rep = _check(M, F, seed=800 + M + F, fmt=fmt)
+    print(f"\nbias+gelu {fmt} M={M} F={F}: {rep}", flush=True)
+
+
+def test_vitb_mlp_activation_of_four_clips_every_element():
+    # 4 clips x 1568 tokens, MLP width 3072 = 4 x 768 (the oracle takes a few seconds on this)
+    rep = _check(4 * 1568, 3072, seed=230916692)
+    print(f"\nbias+gelu vitb: {rep}", flush=True)
+
+
+def test_both_tails_and_large_arguments():
+    # arguments from -12 to 12 in steps of 1/8 (exact in bf16): the left tail must go to -0/0 smoothly and
+    # the right one to the identity; the derivative to 0 and 1
+    import torch
+    import paper_2309_16669_amd as av
+    from oracle import gelu
+    h = np.arange(-96, 97, dtype=np.float32) / np.float32(8.0)
+    F = 200
+    x = np.zeros((1, F), dtype=np.float32)
+    x[0, :len(h)] = h
+    bits = si.f32_to_bf16_bits(x)
+    xt = torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+    bias = torch.zeros((F,), dtype=torch.float32, device="cuda")
+    ones = torch.ones_like(xt)
+    y, dx = torch.empty_like(xt), torch.empty_like(xt)
+    dbias = torch.empty((F,), dtype=torch.float32, device="cuda")
+    ws = torch.empty(av.bias_gelu_bwd_workspace_bytes(1, F), dtype=torch.uint8, device="cuda")
+    av.bias_gelu_fwd(xt, bias, y)
+    av.bias_gelu_bwd(xt, bias, ones, dx, dbias, ws)
+    torch.cuda.synchronize()
+    xf = si.bf16_bits_to_f64(bits)
+    ry, (rdx, rdb) = gelu.fwd(xf, np.zeros(F)), gelu.bwd(xf, np.zeros(F), np.ones((1, F)))
+    assert np.abs(y.double().cpu().numpy() - ry).max() <= 2.0 ** -9 * 12 and np.all(np.abs(y.double().cpu().numpy() - ry) <= 1.01 * 2.0 ** -8 * np.abs(ry) + 2e-6)
+    assert np.all(np.abs(dx.double().cpu().numpy() - rdx) <= 1.01 * 2.0 ** -8 * np.abs(rdx) + 2e-6)
+    assert np.abs(dbias.double().cpu().numpy() - rdb).max() <= 2e-6    # one row: dbias is the unrounded dx
+
+
+def test_bitwise_reproducible():
+    import torch
+    a = _run(3001, 3072, seed=9)[1]
+    b = _run(3001, 3072, seed=9)[1]
+    for n in ("y", "dx"):
+        assert torch.equal(a[n].view(torch.int16), b[n].view(torch.int16)), n
+    assert torch.equal(a["dbias"], b["dbias"])
+
+
+def test_bad_arguments_are_rejected_without_launching():
+    import paper_2309_16669_amd as av
+    lib = av.load_library()
+    fake = ctypes.c_void_p(0x1000)
+
+    def fwd(x=fake, M=4, F=64, flags=0):
+        return lib.avion_bias_gelu_fwd(x, fake, fake, M, F, flags, None)
+    assert fwd(x=None) == av.EINVAL and fwd(M=0) == av.EINVAL and fwd(F=0) == av.EINVAL and fwd(flags=2) == av.EINVAL
+    assert fwd(F=60) == av.EUNSUPPORTED and fwd(F=65544) == av.EUNSUPPORTED and fwd(x=ctypes.c_void_p(0x1004)) == av.EUNSUPPORTED
+    assert av.bias_gelu_bwd_workspace_bytes(10, 60) == 0
+    assert av.bias_gelu_bwd_workspace_bytes(10 ** 6, 3072) == av.bias_gelu_bwd_workspace_bytes(10 ** 7, 3072)   # independent of M
+    assert lib.avion_bias_gelu_bwd(fake, fake, fake, fake, fake, 4, 64, 0, fake, 16, None) == av.EWORKSPACE
