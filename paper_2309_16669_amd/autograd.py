@@ -1,4 +1,4 @@
-"""torch.autograd front end of the attention library, for use inside a training step.
+"""torch.autograd front end of the library, for use inside a training step.
 
 `attention(q, k, v)` and `attention_qkvpacked(qkv)` allocate the outputs and the saved log-sum-exp with
 torch and call the C-ABI entry points of `include/avion_attn.h` (the general forms, so every
@@ -11,6 +11,9 @@ N x N matrix (the memory saving of Sec. 4.1 of the paper).
 
 The backward's workspace is kept per (device, stream) and grown on demand, so a layer's backward does
 not go through the allocator every step; backward calls on one stream are ordered and may share it.
+
+`layer_norm(x, gamma, beta)` and `bias_gelu(x, bias)` wrap the layer-normalisation and bias + GELU
+entry points the same way (what they keep for the backward is stated in their docstrings).
 """
 from __future__ import annotations
 
@@ -18,19 +21,23 @@ import math
 
 import torch
 
-from . import attn_bwd_ex, attn_bwd_workspace_bytes, attn_fwd_ex
+from . import (attn_bwd_ex, attn_bwd_workspace_bytes, attn_fwd_ex, bias_gelu_bwd, bias_gelu_bwd_workspace_bytes, bias_gelu_fwd,
+               layernorm_bwd, layernorm_bwd_workspace_bytes, layernorm_fwd)
 
 _workspaces: dict = {}
 
 
-def _workspace(B, H, N, d, device):
-    need = attn_bwd_workspace_bytes(B, H, N, d)
+def _workspace_of(need, device):
     key = (device, torch.cuda.current_stream(device).cuda_stream)
     ws = _workspaces.get(key)
     if ws is None or ws.numel() < need:
         ws = torch.empty(need, dtype=torch.uint8, device=device)
         _workspaces[key] = ws
     return ws
+
+
+def _workspace(B, H, N, d, device):
+    return _workspace_of(attn_bwd_workspace_bytes(B, H, N, d), device)
 
 
 class _Attention(torch.autograd.Function):
@@ -74,6 +81,65 @@ class _AttentionPacked(torch.autograd.Function):
         attn_bwd_ex(qkv, None, None, o, lse, dO.contiguous(), dqkv, None, None, ctx.scale,
                     _workspace(B, H, N, d, qkv.device), ctx.causal)
         return dqkv, None, None
+
+
+class _LayerNorm(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, x, gamma, beta, eps):
+        shape = x.shape
+        x2 = x.contiguous().view(-1, shape[-1])
+        M = x2.shape[0]
+        y = torch.empty_like(x2)
+        mean = torch.empty((M,), dtype=torch.float32, device=x.device)
+        rstd = torch.empty((M,), dtype=torch.float32, device=x.device)
+        layernorm_fwd(x2, gamma.contiguous(), beta.contiguous(), y, mean, rstd, eps)
+        ctx.save_for_backward(x2, gamma, mean, rstd)   # the input and two floats per token; not y
+        ctx.shape = shape
+        return y.view(shape)
+
+    @staticmethod
+    def backward(ctx, dy):
+        x2, gamma, mean, rstd = ctx.saved_tensors
+        M, D = x2.shape
+        dx = torch.empty_like(x2)
+        dgamma, dbeta = torch.empty_like(gamma), torch.empty_like(gamma)
+        layernorm_bwd(x2, gamma.contiguous(), mean, rstd, dy.contiguous().view(M, D), dx, dgamma, dbeta,
+                      _workspace_of(layernorm_bwd_workspace_bytes(M, D), x2.device))
+        return dx.view(ctx.shape), dgamma, dbeta, None
+
+
+class _BiasGelu(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, x, bias):
+        shape = x.shape
+        x2 = x.contiguous().view(-1, shape[-1])
+        y = torch.empty_like(x2)
+        bias_gelu_fwd(x2, bias.contiguous(), y)
+        ctx.save_for_backward(x2, bias)                # the pre-activation only; the derivative is rebuilt from it
+        ctx.shape = shape
+        return y.view(shape)
+
+    @staticmethod
+    def backward(ctx, dy):
+        x2, bias = ctx.saved_tensors
+        M, F = x2.shape
+        dx, dbias = torch.empty_like(x2), torch.empty_like(bias)
+        bias_gelu_bwd(x2, bias.contiguous(), dy.contiguous().view(M, F), dx, dbias,
+                      _workspace_of(bias_gelu_bwd_workspace_bytes(M, F), x2.device))
+        return dx.view(ctx.shape), dbias
+
+
+def layer_norm(x, gamma, beta, eps: float = 1e-5):
+    """Layer normalisation over the last axis of x (bf16 or fp16, any leading shape, width <= 2048 and a
+    multiple of 8) with fp32 gain and bias.  Differentiable in x, gamma and beta; keeps x and two floats
+    per token for the backward."""
+    return _LayerNorm.apply(x, gamma, beta, float(eps))
+
+
+def bias_gelu(x, bias):
+    """GELU(x + bias) (exact erf form) over the last axis of x (bf16 or fp16, width a multiple of 8) with
+    an fp32 bias.  Differentiable in x and bias; keeps only x for the backward."""
+    return _BiasGelu.apply(x, bias)
 
 
 def attention(q, k, v, scale: float | None = None, causal: bool = False):

@@ -126,3 +126,34 @@ def test_bad_arguments_are_rejected_without_launching():
     assert av.bias_gelu_bwd_workspace_bytes(10, 60) == 0
     assert av.bias_gelu_bwd_workspace_bytes(10 ** 6, 3072) == av.bias_gelu_bwd_workspace_bytes(10 ** 7, 3072)   # independent of M
     assert lib.avion_bias_gelu_bwd(fake, fake, fake, fake, fake, 4, 64, 0, fake, 16, None) == av.EWORKSPACE
+
+
+def test_autograd_front_ends_of_layer_norm_and_bias_gelu():
+    # y = bias_gelu(layer_norm(x), b); loss = sum(y * w): every gradient torch.autograd returns must be the
+    # oracle's chain rule through both steps
+    import torch
+    from oracle import gelu, layernorm as ln
+    from paper_2309_16669_amd import autograd as ag
+    B, N, D = 2, 37, 64
+    inp = si.layernorm_inputs(B * N, D, seed=31)
+    w = si.bf16_bits_to_f64(si.gelu_inputs(B * N, D, seed=32)["dy"])
+    bias = (np.float32(0.1) * si.normal_f32(33, 1, D)).astype(np.float32)
+    up = lambda bits: torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
+    x = up(inp["x"]).view(B, N, D).requires_grad_()
+    gamma = torch.from_numpy(inp["gamma"]).cuda().requires_grad_()
+    beta = torch.from_numpy(inp["beta"]).cuda().requires_grad_()
+    bt = torch.from_numpy(bias).cuda().requires_grad_()
+    h = ag.layer_norm(x, gamma, beta, 1e-5)
+    y = ag.bias_gelu(h, bt)
+    (y.float() * torch.from_numpy(w).cuda().view(B, N, D).float()).sum().backward()
+    # the oracle's chain: the second step sees the first one's output as the kernels rounded it
+    xf = si.bf16_bits_to_f64(inp["x"])
+    hf = h.detach().double().cpu().numpy().reshape(B * N, D)
+    ry = gelu.fwd(hf, bias)
+    rdh, rdb = gelu.bwd(hf, bias, w)
+    dh_rounded = si.bf16_bits_to_f64(si.f32_to_bf16_bits(rdh.astype(np.float32)))   # what arrives at layer_norm's backward
+    rdx, rdg, rdbeta = ln.bwd(xf, inp["gamma"], dh_rounded, 1e-5)
+    u = 2.0 ** -8
+    close = lambda got, ref, tol: np.abs(got.double().cpu().numpy().reshape(ref.shape) - ref).max() <= tol * max(np.abs(ref).max(), 1e-30)
+    assert close(y.detach(), ry, 1.01 * u)
+    assert close(x.grad, rdx, 3 * u) and close(bt.grad, rdb, 1e-4) and close(gamma.grad, rdg, 2e-3) and close(beta.grad, rdbeta, 2e-3)
