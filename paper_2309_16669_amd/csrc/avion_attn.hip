@@ -425,6 +425,8 @@ int gelu_check(long long M, int F, unsigned flags)
 struct GeluGrid {
     int ncb, nrg;
 };
+// tensors beyond half of the 256 MB last-level cache are streamed past it
+bool gelu_streams(long long M, int F) { return M * F * 2 > (128LL << 20); }
 GeluGrid gelu_grid(long long M, int F)
 {
     GeluGrid g;
@@ -667,13 +669,17 @@ int avion_bias_gelu_fwd(const void* x, const float* bias, void* y, long long M, 
     if (!aligned16(x) || !aligned16(y) || !aligned16(bias)) return AVION_EUNSUPPORTED;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const GeluGrid g = gelu_grid(M, F);
+    const bool f16 = (flags & AVION_FLAG_F16) != 0, stream_past_cache = gelu_streams(M, F);
+    auto launch = [&](auto fmt, auto streaming) {
+        hipLaunchKernelGGL((avion_bias_gelu_fwd_kernel<typename decltype(fmt)::type, decltype(streaming)::value>),
+                           dim3((unsigned)(g.ncb * g.nrg)), dim3(kGeluThreads), 0, st, static_cast<const raw16*>(x), bias,
+                           static_cast<raw16*>(y), (long)M, F, g.ncb);
+    };
     begin_launch();
-    if (flags & AVION_FLAG_F16)
-        hipLaunchKernelGGL(avion_bias_gelu_fwd_kernel<F16>, dim3((unsigned)(g.ncb * g.nrg)), dim3(kGeluThreads), 0, st,
-                           static_cast<const raw16*>(x), bias, static_cast<raw16*>(y), (long)M, F, g.ncb);
-    else
-        hipLaunchKernelGGL(avion_bias_gelu_fwd_kernel<Bf16>, dim3((unsigned)(g.ncb * g.nrg)), dim3(kGeluThreads), 0, st,
-                           static_cast<const raw16*>(x), bias, static_cast<raw16*>(y), (long)M, F, g.ncb);
+    if (f16 && stream_past_cache) launch(TypeTag<F16>{}, std::true_type{});
+    else if (f16) launch(TypeTag<F16>{}, std::false_type{});
+    else if (stream_past_cache) launch(TypeTag<Bf16>{}, std::true_type{});
+    else launch(TypeTag<Bf16>{}, std::false_type{});
     return end_launch("launch avion_bias_gelu_fwd_kernel");
 }
 
@@ -692,15 +698,17 @@ int avion_bias_gelu_bwd(const void* x, const float* bias, const void* dy, void* 
     hipStream_t st = static_cast<hipStream_t>(stream);
     float* part = static_cast<float*>(workspace);
     const GeluGrid g = gelu_grid(M, F);
+    const bool f16 = (flags & AVION_FLAG_F16) != 0, stream_past_cache = gelu_streams(M, F);
+    auto launch = [&](auto fmt, auto streaming) {
+        hipLaunchKernelGGL((avion_bias_gelu_bwd_kernel<typename decltype(fmt)::type, decltype(streaming)::value>),
+                           dim3((unsigned)(g.ncb * g.nrg)), dim3(kGeluThreads), 0, st, static_cast<const raw16*>(x), bias,
+                           static_cast<const raw16*>(dy), static_cast<raw16*>(dx), part, (long)M, F, g.ncb);
+    };
     begin_launch();
-    if (flags & AVION_FLAG_F16)
-        hipLaunchKernelGGL(avion_bias_gelu_bwd_kernel<F16>, dim3((unsigned)(g.ncb * g.nrg)), dim3(kGeluThreads), 0, st,
-                           static_cast<const raw16*>(x), bias, static_cast<const raw16*>(dy), static_cast<raw16*>(dx), part,
-                           (long)M, F, g.ncb);
-    else
-        hipLaunchKernelGGL(avion_bias_gelu_bwd_kernel<Bf16>, dim3((unsigned)(g.ncb * g.nrg)), dim3(kGeluThreads), 0, st,
-                           static_cast<const raw16*>(x), bias, static_cast<const raw16*>(dy), static_cast<raw16*>(dx), part,
-                           (long)M, F, g.ncb);
+    if (f16 && stream_past_cache) launch(TypeTag<F16>{}, std::true_type{});
+    else if (f16) launch(TypeTag<F16>{}, std::false_type{});
+    else if (stream_past_cache) launch(TypeTag<Bf16>{}, std::true_type{});
+    else launch(TypeTag<Bf16>{}, std::false_type{});
     const int r1 = end_launch("launch avion_bias_gelu_bwd_kernel");
     if (r1 != AVION_OK) return r1;
     // column sums of the row groups' partials: the reduction kernel splits its 2 * (F / 2) columns into two outputs

@@ -13,6 +13,11 @@
 // and walks the rows of its row group with a stride, four rows in flight.  The partial sums of the row
 // groups are added by avion_ln_param_reduce_kernel in a fixed order: no atomics, bit-reproducible.
 //
+// Tensors much larger than the chip's last-level cache (256 MB) are read and written with
+// nontemporal accesses (STREAM): nothing of them will be found there again, and keeping them out of it
+// is worth 4 % (forward) and 7 % (backward) on [50176, 3072]; smaller tensors take ordinary accesses,
+// so that a consumer right after finds them cached.
+//
 // erf: 1 - erf(z) = t (a1 + t (a2 + t (a3 + t (a4 + t a5)))) exp(-z^2), t = 1 / (1 + p z), z >= 0
 // (Abramowitz and Stegun 7.1.26, absolute error < 1.5e-7, far below the rounding of the outputs);
 // its exponential exp(-z^2) = exp(-h^2 / 2) is the one phi(h) needs, so each element costs one
@@ -23,6 +28,20 @@
 constexpr int kGeluThreads = 128;     // threads per workgroup = 16-byte column chunks per workgroup
 constexpr int kGeluRows = 4;          // rows in flight per thread
 constexpr int kGeluMaxGrid = 4096;    // workgroups of a launch (column blocks x row groups)
+
+template <bool STREAM>
+DEVINL u32x4 gelu_load(const raw16* p)
+{
+    const u32x4* q = reinterpret_cast<const u32x4*>(p);
+    return STREAM ? __builtin_nontemporal_load(q) : *q;
+}
+template <bool STREAM>
+DEVINL void gelu_store(raw16* p, u32x4 v)
+{
+    u32x4* q = reinterpret_cast<u32x4*>(p);
+    if (STREAM) __builtin_nontemporal_store(v, q);
+    else *q = v;
+}
 
 // Phi(h) and h * phi(h)
 DEVINL void gelu_terms(float h, float& cdf, float& hpdf)
@@ -40,7 +59,7 @@ DEVINL void gelu_terms(float h, float& cdf, float& hpdf)
 }
 
 // ncb = column blocks; gridDim.x = ncb * (row groups)
-template <typename E>
+template <typename E, bool STREAM>
 __global__ void __launch_bounds__(kGeluThreads)
 avion_bias_gelu_fwd_kernel(const raw16* __restrict__ x, const float* __restrict__ bias, raw16* __restrict__ y, long M, int F,
                            int ncb)
@@ -57,7 +76,7 @@ avion_bias_gelu_fwd_kernel(const raw16* __restrict__ x, const float* __restrict_
 #pragma unroll
         for (int k = 0; k < kGeluRows; ++k) {
             const long row = r + k * nrg;
-            if (row < M) in[k] = *reinterpret_cast<const u32x4*>(x + row * F + col);
+            if (row < M) in[k] = gelu_load<STREAM>(x + row * F + col);
         }
 #pragma unroll
         for (int k = 0; k < kGeluRows; ++k) {
@@ -74,14 +93,14 @@ avion_bias_gelu_fwd_kernel(const raw16* __restrict__ x, const float* __restrict_
                 u32x4 w;
 #pragma unroll
                 for (int p = 0; p < 4; ++p) w[p] = E::pack(o[2 * p], o[2 * p + 1]);
-                *reinterpret_cast<u32x4*>(y + row * F + col) = w;
+                gelu_store<STREAM>(y + row * F + col, w);
             }
         }
     }
 }
 
 // dx, and this row group's partial sums of dbias into part[row group][F]
-template <typename E>
+template <typename E, bool STREAM>
 __global__ void __launch_bounds__(kGeluThreads)
 avion_bias_gelu_bwd_kernel(const raw16* __restrict__ x, const float* __restrict__ bias, const raw16* __restrict__ dy,
                            raw16* __restrict__ dx, float* __restrict__ part, long M, int F, int ncb)
@@ -102,8 +121,8 @@ avion_bias_gelu_bwd_kernel(const raw16* __restrict__ x, const float* __restrict_
         for (int k = 0; k < kGeluRows; ++k) {
             const long row = r + k * nrg;
             if (row < M) {
-                in[k] = *reinterpret_cast<const u32x4*>(x + row * F + col);
-                gin[k] = *reinterpret_cast<const u32x4*>(dy + row * F + col);
+                in[k] = gelu_load<STREAM>(x + row * F + col);
+                gin[k] = gelu_load<STREAM>(dy + row * F + col);
             }
         }
 #pragma unroll
@@ -122,7 +141,7 @@ avion_bias_gelu_bwd_kernel(const raw16* __restrict__ x, const float* __restrict_
                 u32x4 w;
 #pragma unroll
                 for (int p = 0; p < 4; ++p) w[p] = E::pack(o[2 * p], o[2 * p + 1]);
-                *reinterpret_cast<u32x4*>(dx + row * F + col) = w;
+                gelu_store<STREAM>(dx + row * F + col, w);
             }
         }
     }

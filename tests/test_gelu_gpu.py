@@ -78,6 +78,40 @@ def test_vitb_mlp_activation_of_four_clips_every_element():
     print(f"\nbias+gelu vitb: {rep}", flush=True)
 
 
+def test_tensors_beyond_the_cache_take_the_streaming_instances():
+    # above 128 MB per tensor the kernels read and write with nontemporal accesses: same results.
+    # [22016, 3072] is 135 MB per tensor; the oracle runs over blocks of rows
+    import torch
+    import paper_2309_16669_amd as av
+    from oracle import gelu
+    M, F = 22016, 3072
+    g = torch.Generator(device="cuda")
+    g.manual_seed(4)
+    x = (1.5 * torch.randn((M, F), device="cuda", generator=g)).bfloat16()
+    dy = torch.randn((M, F), device="cuda", generator=g).bfloat16()
+    bias = 0.1 * torch.randn((F,), device="cuda", generator=g)
+    y, dx = torch.full_like(x, float("nan")), torch.full_like(x, float("nan"))
+    dbias = torch.full((F,), float("nan"), dtype=torch.float32, device="cuda")
+    ws = torch.empty(av.bias_gelu_bwd_workspace_bytes(M, F), dtype=torch.uint8, device="cuda")
+    av.bias_gelu_fwd(x, bias, y)
+    av.bias_gelu_bwd(x, bias, dy, dx, dbias, ws)
+    torch.cuda.synchronize()
+    b64 = bias.double().cpu().numpy()
+    rdb = np.zeros(F)
+    u = 2.0 ** -8
+    for r0 in range(0, M, 2752):
+        sl = slice(r0, min(M, r0 + 2752))
+        xs, dys = x[sl].double().cpu().numpy(), dy[sl].double().cpu().numpy()
+        ry = gelu.fwd(xs, b64)
+        rdx, part = gelu.bwd(xs, b64, dys)
+        rdb += part
+        for got, ref in ((y[sl], ry), (dx[sl], rdx)):
+            err = np.abs(got.double().cpu().numpy() - ref)
+            assert np.all(err <= 1.01 * u * np.abs(ref) + 1e-5), (r0, float(err.max()))
+    rel = np.sqrt(((dbias.double().cpu().numpy() - rdb) ** 2).sum() / (rdb ** 2).sum())
+    assert rel <= 1e-4, rel
+
+
 def test_both_tails_and_large_arguments():
     # arguments from -12 to 12 in steps of 1/8 (exact in bf16): the left tail must go to -0/0 smoothly and
     # the right one to the identity; the derivative to 0 and 1
