@@ -37,18 +37,18 @@ MEASURED_HBM_BYTES_PER_LAUNCH = {
     # (workload, dtype, kernel) -> (bytes per launch, summary under profiles/ that holds the counters):
     # (2.0 x FETCH_SIZE + 1.0 x WRITE_SIZE) KiB, the factors being what the same counters read for a plain copy of
     # known size.  Measured offline on separate q/k/v tensors with N(0,1) operands; any other run prints null.
-    ("vitb_batch", "bf16", "avion_fwd_kernel"): (3.1236e+08, "profiles/vitb_batch_bf16.txt"),
-    ("vitb_batch", "bf16", "avion_dq_kernel"): (4.7273e+08, "profiles/vitb_batch_bf16.txt"),
-    ("vitb_batch", "bf16", "avion_dkdv_kernel"): (5.1175e+08, "profiles/vitb_batch_bf16.txt"),
-    ("vitb_batch", "f16", "avion_fwd_kernel"): (3.1248e+08, "profiles/vitb_batch_f16.txt"),
-    ("vitb_batch", "f16", "avion_dq_kernel"): (4.7330e+08, "profiles/vitb_batch_f16.txt"),
-    ("vitb_batch", "f16", "avion_dkdv_kernel"): (5.1204e+08, "profiles/vitb_batch_f16.txt"),
-    ("vith_d80", "bf16", "avion_fwd_kernel"): (1.3885e+08, "profiles/vith_d80.txt"),
-    ("vith_d80", "bf16", "avion_dq_kernel"): (2.1919e+08, "profiles/vith_d80.txt"),
-    ("vith_d80", "bf16", "avion_dkdv_kernel"): (2.2141e+08, "profiles/vith_d80.txt"),
-    ("vitb_long", "bf16", "avion_fwd_kernel"): (1.5898e+08, "profiles/vitb_long.txt"),
-    ("vitb_long", "bf16", "avion_dq_kernel"): (2.4761e+08, "profiles/vitb_long.txt"),
-    ("vitb_long", "bf16", "avion_dkdv_kernel"): (2.6611e+08, "profiles/vitb_long.txt"),
+    ("vitb_batch", "bf16", "avion_fwd_kernel"): (3.1232e+08, "profiles/vitb_batch_bf16.txt"),
+    ("vitb_batch", "bf16", "avion_dq_kernel"): (4.7268e+08, "profiles/vitb_batch_bf16.txt"),
+    ("vitb_batch", "bf16", "avion_dkdv_kernel"): (4.7071e+08, "profiles/vitb_batch_bf16.txt"),
+    ("vitb_batch", "f16", "avion_fwd_kernel"): (3.1226e+08, "profiles/vitb_batch_f16.txt"),
+    ("vitb_batch", "f16", "avion_dq_kernel"): (4.7278e+08, "profiles/vitb_batch_f16.txt"),
+    ("vitb_batch", "f16", "avion_dkdv_kernel"): (4.7065e+08, "profiles/vitb_batch_f16.txt"),
+    ("vith_d80", "bf16", "avion_fwd_kernel"): (1.3886e+08, "profiles/vith_d80.txt"),
+    ("vith_d80", "bf16", "avion_dq_kernel"): (2.1884e+08, "profiles/vith_d80.txt"),
+    ("vith_d80", "bf16", "avion_dkdv_kernel"): (2.2160e+08, "profiles/vith_d80.txt"),
+    ("vitb_long", "bf16", "avion_fwd_kernel"): (1.5843e+08, "profiles/vitb_long.txt"),
+    ("vitb_long", "bf16", "avion_dq_kernel"): (2.4605e+08, "profiles/vitb_long.txt"),
+    ("vitb_long", "bf16", "avion_dkdv_kernel"): (2.4492e+08, "profiles/vitb_long.txt"),
 }
 PREWARM_SECONDS = 0.3
 

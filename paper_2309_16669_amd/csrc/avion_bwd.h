@@ -307,8 +307,9 @@ DEVINL void avion_dkdv_body(char* smem, const raw16* __restrict__ q, const raw16
     }
     if (!wave_active) return;
     char* region = smem + wave * RowStore<D, E>::BYTES;
-    RowStore<D, E>::run(region, dka, scale, dk + head_off + (long)k0 * rs, rs, N - k0, lane);
-    RowStore<D, E>::run(region, dva, 1.0f, dv + head_off + (long)k0 * rs, rs, N - k0, lane);
+    const int lane_now = lane_from_exec();
+    RowStore<D, E>::run(region, dka, scale, dk + head_off + (long)k0 * rs, rs, N - k0, lane_now);
+    RowStore<D, E>::run(region, dva, 1.0f, dv + head_off + (long)k0 * rs, rs, N - k0, lane_now);
 }
 
 template <int D, int NW, typename E, bool CAUSAL>

@@ -143,6 +143,9 @@ DEVINL float both_halves_sum(float x)
 // Wait until every outstanding global/buffer load of this wavefront has returned (vmcnt(0)).
 // Placed once before a main loop so that loads issued in the prologue are not waited for again
 // inside the loop, where the same counter also covers the tile prefetch that should stay in flight.
+// lane index from the execution mask: costs two instructions where it is used and keeps no register alive before that
+DEVINL int lane_from_exec() { return (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u)); }
+
 DEVINL void wait_all_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 
 DEVINL float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }

@@ -265,6 +265,6 @@ avion_fwd_kernel(const raw16* __restrict__ q, const raw16* __restrict__ k, const
     for (int ct = 0; ct < CT; ++ct)
 #pragma unroll
         for (int i = 0; i < 16; ++i) oacc[ct][i] *= inv;
-    RowStore<D, E>::run(smem + wave * RowStore<D, E>::BYTES, oacc, 1.0f, o + head_off_o + (long)q0 * rs_o, rs_o, N - q0, lane);
+    RowStore<D, E>::run(smem + wave * RowStore<D, E>::BYTES, oacc, 1.0f, o + head_off_o + (long)q0 * rs_o, rs_o, N - q0, lane_from_exec());
     if (g == 0 && q0 + l32 < N) lse[(long)bh * N + q0 + l32] = (m_used + __builtin_amdgcn_logf(l)) * kLn2;
 }
