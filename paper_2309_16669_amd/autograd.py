@@ -129,6 +129,44 @@ class _BiasGelu(torch.autograd.Function):
         return dx.view(ctx.shape), dbias
 
 
+class _BiasGeluLinear(torch.autograd.Function):
+    """linear(GELU(x + bias), weight, out_bias) that keeps x only: the activation's output is rebuilt in the
+    backward pass (one more avion_bias_gelu_fwd) for the weight gradient.  The two matrix products per
+    direction are torch's (library GEMMs)."""
+
+    @staticmethod
+    def forward(ctx, x, bias, weight, out_bias):
+        shape = x.shape
+        x2 = x.contiguous().view(-1, shape[-1])
+        y = torch.empty_like(x2)
+        bias_gelu_fwd(x2, bias.contiguous(), y)
+        out = torch.addmm(out_bias, y, weight.t()) if out_bias is not None else y @ weight.t()
+        ctx.save_for_backward(x2, bias, weight)
+        ctx.shape, ctx.has_out_bias = shape, out_bias is not None
+        return out.view(*shape[:-1], weight.shape[0])
+
+    @staticmethod
+    def backward(ctx, dout):
+        x2, bias, weight = ctx.saved_tensors
+        M, F = x2.shape
+        d2 = dout.contiguous().view(M, weight.shape[0])
+        y = torch.empty_like(x2)
+        bias_gelu_fwd(x2, bias.contiguous(), y)          # rebuilt, not kept
+        dweight = d2.t() @ y
+        dy = d2 @ weight
+        del y
+        dx, dbias = torch.empty_like(x2), torch.empty_like(bias)
+        bias_gelu_bwd(x2, bias.contiguous(), dy, dx, dbias, _workspace_of(bias_gelu_bwd_workspace_bytes(M, F), x2.device))
+        return dx.view(ctx.shape), dbias, dweight, (d2.sum(0) if ctx.has_out_bias else None)
+
+
+def bias_gelu_linear(x, bias, weight, out_bias=None):
+    """linear(GELU(x + bias), weight, out_bias): the second half of the encoder's MLP, keeping only x (the
+    first matrix product's output) for the backward; x bf16 or fp16 [..., F], bias fp32 [F], weight
+    [out, F] and out_bias [out] in the format of x."""
+    return _BiasGeluLinear.apply(x, bias, weight, out_bias)
+
+
 def layer_norm(x, gamma, beta, eps: float = 1e-5):
     """Layer normalisation over the last axis of x (bf16 or fp16, any leading shape, width <= 2048 and a
     multiple of 8) with fp32 gain and bias.  Differentiable in x, gamma and beta; keeps x and two floats

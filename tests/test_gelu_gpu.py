@@ -191,3 +191,55 @@ def test_autograd_front_ends_of_layer_norm_and_bias_gelu():
     close = lambda got, ref, tol: np.abs(got.double().cpu().numpy().reshape(ref.shape) - ref).max() <= tol * max(np.abs(ref).max(), 1e-30)
     assert close(y.detach(), ry, 1.01 * u)
     assert close(x.grad, rdx, 3 * u) and close(bt.grad, rdb, 1e-4) and close(gamma.grad, rdg, 2e-3) and close(beta.grad, rdbeta, 2e-3)
+
+
+def test_bias_gelu_linear_keeps_only_the_pre_activation_and_matches_the_chain_rule():
+    # out = GELU(h + b) W^T + c with the activation's output rebuilt in the backward pass
+    import torch
+    from oracle import gelu
+    from paper_2309_16669_amd import autograd as ag
+    M, F, O = 70, 256, 64
+    inp = si.gelu_inputs(M, F, seed=41)
+    up = lambda bits: torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
+    h = up(inp["x"]).requires_grad_()
+    b = torch.from_numpy(inp["bias"]).cuda().requires_grad_()
+    wbits = si.f32_to_bf16_bits((np.float32(0.05) * si.normal_f32(42, 1, O * F)).astype(np.float32)).reshape(O, F)
+    cbits = si.f32_to_bf16_bits((np.float32(0.1) * si.normal_f32(42, 2, O)).astype(np.float32))
+    gbits = si.f32_to_bf16_bits(si.normal_f32(42, 3, M * O)).reshape(M, O)
+    W, c, dout = up(wbits).requires_grad_(), up(cbits).requires_grad_(), up(gbits)
+    saved = []
+    with torch.autograd.graph.saved_tensors_hooks(lambda t: (saved.append(tuple(t.shape)), t)[1], lambda t: t):
+        out = ag.bias_gelu_linear(h, b, W, c)
+    assert (M, F) in saved and saved.count((M, F)) == 1          # the pre-activation, once; not the activation's output
+    out.backward(dout)
+    hf, Wf, cf, gf = (si.bf16_bits_to_f64(a) for a in (inp["x"], wbits, cbits, gbits))
+    y = gelu.fwd(hf, inp["bias"])
+    y_r = si.bf16_bits_to_f64(si.f32_to_bf16_bits(y.astype(np.float32)))      # the kernel's output as the product sees it
+    ref_out = y_r @ Wf.T + cf
+    dy = gf @ Wf
+    dy_r = si.bf16_bits_to_f64(si.f32_to_bf16_bits(dy.astype(np.float32)))
+    rdh, rdb = gelu.bwd(hf, inp["bias"], dy_r)
+    rdW, rdc = gf.T @ y_r, gf.sum(0)
+    close = lambda got, ref, tol: np.abs(got.double().cpu().numpy() - ref).max() <= tol * max(np.abs(ref).max(), 1e-30)
+    u = 2.0 ** -8
+    assert close(out.detach(), ref_out, 3 * u) and close(h.grad, rdh, 3 * u) and close(b.grad, rdb, 2e-3)
+    assert close(W.grad, rdW, 3 * u) and close(c.grad, rdc, 3 * u)
+
+
+def test_memory_profile_of_a_small_encoder():
+    # the accounting script on 2 layers of width 128: with the library's attention nothing N x N is kept
+    from paper_2309_16669_amd import memory_profile as mp
+    import torch
+    N, B, L, W, H = 200, 2, 2, 128, 2
+    res = mp.profile(tokens=N, batch=B, layers=L, width=W, heads=H, dtype=torch.bfloat16, steps=1)["variants"]
+    MB = 1e6
+    ln = L * 2 * N * (2 * W + 8) / MB                        # input and two floats per token, two norms per layer
+    assert abs(res["plain"]["saved_MB_per_video"]["LayerNorm"] - ln) < 1e-6 + 0.01 * ln
+    assert abs(res["all kernels"]["saved_MB_per_video"]["LayerNorm"] - ln) < 1e-6
+    nxn = L * H * N * N * 2 / MB                             # one N x N tensor per head and layer in 2-byte elements
+    own = L * (N * W * 2 * 5 + H * N * 4) / MB               # projections' inputs, q, k, v, o; one fp32 per head and token
+    assert res["plain"]["saved_MB_per_video"]["MHA"] >= own - L * H * N * 4 / MB + nxn - 1e-6
+    assert abs(res["attention"]["saved_MB_per_video"]["MHA"] - own) < 1e-6
+    mlp_plain, mlp_ours = res["plain"]["saved_MB_per_video"]["MLP"], res["all kernels"]["saved_MB_per_video"]["MLP"]
+    assert abs(mlp_plain - L * N * W * 2 * 9 / MB) < 1e-6 and abs(mlp_ours - L * N * W * 2 * 5 / MB) < 1e-6
+    assert res["checkpoint"]["peak_activation_MB_per_video"] < res["all kernels"]["peak_activation_MB_per_video"]
