@@ -126,6 +126,7 @@ def main():
                     help="draw the N(0,1) inputs with the device's generator instead of the seeded recipe (same "
                          "distribution, seconds instead of minutes for the large small-sequence workloads; for "
                          "profiling runs -- the CPU baseline is skipped)")
+    ap.add_argument("--no-other-format", action="store_true", help="skip the fp16 block of a bf16 run")
     ap.add_argument("--no-layernorm", action="store_true", help="skip the layer-normalisation and bias + GELU blocks of the line")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain device copy of Q (known size) so that HBM counters of a "
@@ -315,6 +316,21 @@ def main():
             "ms_per_step": ms_ckpt, "slowdown_vs_plain_step": ms_ckpt / ms_step,
             "note": "fwd + fwd + bwd; still 14*B*H*N^2*d useful flops",
             "tflops_useful": tf(14 * base, ms_ckpt)}
+    if not f16 and not args.no_other_format and args.operands == "recipe":
+        # the same step on fp16 tensors (the format the paper measured in), values of the same draws
+        hq, hk, hv, hdO = (t.to(torch.float16) for t in (q, k, v, dO))
+        ho, hdq, hdk, hdv = (torch.empty_like(hq) for _ in range(4))
+
+        def step_f16():
+            if packed:
+                return
+            av.attn_fwd_ex(hq, hk, hv, ho, lse, w.scale, args.causal, stream)
+            av.attn_bwd_ex(hq, hk, hv, ho, lse, hdO, hdq, hdk, hdv, w.scale, ws, args.causal, stream)
+        if not packed:
+            ms_h = timed(step_f16, args.steps, 5, stream)
+            out["fp16_entry_points"] = {"ms_per_step": ms_h, "tflops": tf(14 * base, ms_h),
+                                        "note": "same step through the fp16 instances; not part of `value`"}
+        del hq, hk, hv, hdO, ho, hdq, hdk, hdv
     if not args.no_layernorm:
         # the layer's normalisation on the same tokens ([B*N, H*d], same format): bound by HBM bandwidth;
         # algorithmic bytes: forward reads x and writes y (2 x 2 bytes per element), backward reads x and
