@@ -133,8 +133,8 @@ def main():
                          "rocprofv3 --pmc run can be scaled")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py: this build runs on ONE GPU (attention shards over batch and heads with no "
-                 "exchange; see DESIGN.md). Run with --gpus 1.")
+        sys.exit("bench.py: this build runs on ONE GPU (every (batch, head) pair is an independent problem, so "
+                 "more GPUs would each take a share of the batch with no exchange). Run with --gpus 1.")
 
     import torch
     import synth_inputs as si
