@@ -243,3 +243,56 @@ def test_memory_profile_of_a_small_encoder():
     mlp_plain, mlp_ours = res["plain"]["saved_MB_per_video"]["MLP"], res["all kernels"]["saved_MB_per_video"]["MLP"]
     assert abs(mlp_plain - L * N * W * 2 * 9 / MB) < 1e-6 and abs(mlp_ours - L * N * W * 2 * 5 / MB) < 1e-6
     assert res["checkpoint"]["peak_activation_MB_per_video"] < res["all kernels"]["peak_activation_MB_per_video"]
+
+
+def test_layer_norm_and_bias_gelu_can_be_captured_in_a_graph_and_replayed():
+    # these entry points only enqueue kernels on the caller's stream (no allocation, no memset, no
+    # synchronisation); every replay of a captured forward + backward, with eager work and fresh inputs
+    # in between, must give the bits of the eager calls
+    import torch
+    import paper_2309_16669_amd as av
+    M, D, F = 1500, 768, 3072
+    up = lambda bits: torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
+
+    def tensors(seed):
+        a, b = si.layernorm_inputs(M, D, seed), si.gelu_inputs(M, F, seed)
+        return dict(x=up(a["x"]), dy=up(a["dy"]), gamma=torch.from_numpy(a["gamma"]).cuda(), beta=torch.from_numpy(a["beta"]).cuda(),
+                    h=up(b["x"]), dh=up(b["dy"]), bias=torch.from_numpy(b["bias"]).cuda())
+
+    def outputs():
+        return dict(y=torch.empty((M, D), dtype=torch.bfloat16, device="cuda"), dx=torch.empty((M, D), dtype=torch.bfloat16, device="cuda"),
+                    mean=torch.empty(M, device="cuda"), rstd=torch.empty(M, device="cuda"), dgamma=torch.empty(D, device="cuda"),
+                    dbeta=torch.empty(D, device="cuda"), g=torch.empty((M, F), dtype=torch.bfloat16, device="cuda"),
+                    dg=torch.empty((M, F), dtype=torch.bfloat16, device="cuda"), dbias=torch.empty(F, device="cuda"))
+    lws = torch.empty(av.layernorm_bwd_workspace_bytes(M, D), dtype=torch.uint8, device="cuda")
+    gws = torch.empty(av.bias_gelu_bwd_workspace_bytes(M, F), dtype=torch.uint8, device="cuda")
+
+    def run(t, o):
+        av.layernorm_fwd(t["x"], t["gamma"], t["beta"], o["y"], o["mean"], o["rstd"], 1e-5)
+        av.layernorm_bwd(t["x"], t["gamma"], o["mean"], o["rstd"], t["dy"], o["dx"], o["dgamma"], o["dbeta"], lws)
+        av.bias_gelu_fwd(t["h"], t["bias"], o["g"])
+        av.bias_gelu_bwd(t["h"], t["bias"], t["dh"], o["dg"], o["dbias"], gws)
+    ins = [tensors(600 + i) for i in range(3)]
+    refs = []
+    for t in ins:
+        o = outputs()
+        run(t, o)
+        torch.cuda.synchronize()
+        refs.append({k: v.clone() for k, v in o.items()})
+    cap_in, cap_out = {k: v.clone() for k, v in ins[0].items()}, outputs()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run(cap_in, cap_out)
+    for i in (1, 2, 0, 1):
+        for k in cap_in:
+            cap_in[k].copy_(ins[i][k])
+        for v in cap_out.values():
+            v.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for k, v in cap_out.items():
+            a, b = (v.view(torch.int16), refs[i][k].view(torch.int16)) if v.dtype == torch.bfloat16 else (v, refs[i][k])
+            assert torch.equal(a, b), (i, k)
+        run(ins[(i + 1) % 3], outputs())                      # unrelated eager work between replays
